@@ -1,0 +1,205 @@
+/*
+ * wk.h -- C ABI of the WorldKV hot path for AMD MI355X (gfx950).
+ *
+ * One call = one transformer layer.  The paper's method (Sec. 4) keeps evicted
+ * KV-cache chunks in a store, prunes each chunk by key-key similarity to its
+ * anchor frame when it is stored (World Compression, Sec. 4.3), selects the
+ * Top-k stored chunks by camera/action correspondence when a new chunk is
+ * generated (World Retrieval, Sec. 4.2, Eq. 4), inserts them into the sliding
+ * window without re-encoding, and runs ordinary softmax attention of the
+ * denoising chunk's queries over that window.
+ *
+ * Conventions for every call
+ *   - Tensors are head-major and dense: [H][N][d] with d = 128 contiguous.
+ *     Element types: WK_F32 (IEEE binary32) or WK_BF16 (bfloat16).
+ *   - "device" pointers must be readable/writable by kernels on the current
+ *     HIP device (HBM, or host memory allocated pinned+mapped where stated).
+ *     "host" pointers are ordinary host memory read during the call.
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing and keeps no pointer after a call returns.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns without waiting for it.
+ *   - Argument errors are detected before anything is launched, leave all
+ *     outputs untouched and are returned as a wk_status.  A failed launch
+ *     returns WK_ERR_HIP.  Nothing throws across this boundary.
+ *   - Inputs must be finite; NaN/Inf give unspecified selections.
+ */
+#ifndef WK_H
+#define WK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WK_OK = 0,
+    WK_ERR_INVALID_ARG = 1, /* null pointer, negative size, unknown enum value */
+    WK_ERR_SHAPE = 2,       /* sizes inconsistent with each other (e.g. window too small) */
+    WK_ERR_RATIO = 3,       /* keep ratio outside what the chunk allows */
+    WK_ERR_WORKSPACE = 4,   /* workspace missing or too small */
+    WK_ERR_UNSUPPORTED = 5, /* valid request this build has no kernel for (d != 128, M too large) */
+    WK_ERR_HIP = 6          /* the HIP runtime reported an error */
+} wk_status;
+
+typedef enum { WK_F32 = 0, WK_BF16 = 1 } wk_dtype;
+
+/* Eq. 5 speaks of "key vectors at a given layer" and never of heads.
+ * SHARED: the key vector of a token is the concatenation of its H head slices and one
+ *         index set serves the whole layer (the literal reading; default).
+ * INDEPENDENT: Eq. 5 is applied per head (d = 128) and every head keeps its own,
+ *         equally sized, index set. */
+typedef enum { WK_HEADS_SHARED = 0, WK_HEADS_INDEPENDENT = 1 } wk_head_mode;
+
+/* FIRST_FRAME: the anchor is the first of the chunk's F frames (Sec. 4.3) and is stored in full.
+ * EXTERNAL: the anchor frame is passed separately and is not stored with the chunk; all F*T
+ *         tokens are candidates (needed for one-frame chunks). */
+typedef enum { WK_ANCHOR_FIRST_FRAME = 0, WK_ANCHOR_EXTERNAL = 1 } wk_anchor_mode;
+
+/* CHUNK: rho is the kept fraction of the whole stored chunk (0.5 for "3 frames -> 1.5").
+ * NONANCHOR: rho is the paper's P, the kept fraction of the pooled non-anchor tokens (0.25). */
+typedef enum { WK_RATIO_CHUNK = 0, WK_RATIO_NONANCHOR = 1 } wk_ratio_kind;
+
+/* Two ways to evaluate Eq. 5 (same result up to rounding).
+ * FACTORED: mean cosine = dot product with the mean of the normalised anchor keys; one pass
+ *         over K, bound by HBM bandwidth (default).
+ * GEMM:   token-by-anchor similarity tiles on the matrix cores with the row mean taken in the
+ *         tile epilogue; the T x (F-1)T matrix is never written.  bf16 only. */
+typedef enum { WK_SCORE_FACTORED = 0, WK_SCORE_GEMM = 1 } wk_score_algo;
+
+/* How each distance term is "normalized across the retrieval candidate set" (Sec. 5.1). */
+typedef enum { WK_NORM_MAX = 0, WK_NORM_MINMAX = 1, WK_NORM_MEAN = 2 } wk_norm_mode;
+
+typedef struct wk_compress_desc {
+    int32_t H;           /* heads */
+    int32_t d;           /* head dimension, must be 128 */
+    int32_t T;           /* tokens per latent frame */
+    int32_t F;           /* frames per chunk */
+    int32_t batch;       /* independent chunk-layers in this call (>= 1) */
+    int32_t dtype;       /* wk_dtype */
+    int32_t head_mode;   /* wk_head_mode */
+    int32_t anchor_mode; /* wk_anchor_mode */
+    int32_t ratio_kind;  /* wk_ratio_kind */
+    int32_t score_algo;  /* wk_score_algo */
+    float rho;           /* keep ratio in [0, 1] */
+} wk_compress_desc;
+
+/* Token counts of a compressed chunk (Sec. 4.3: anchor tokens plus the retained tokens; F = 3,
+ * P = 25% gives 3T -> 1.5T).  Counts round half away from zero.  Pure host arithmetic.
+ * Writes the stored tokens per chunk to *n_out and the retained non-anchor tokens to *n_keep
+ * (either may be NULL).  WK_ERR_RATIO if rho is outside [0,1], asks for fewer tokens than the
+ * anchor frame, or leaves the chunk empty. */
+wk_status wk_keep_count(float rho, int32_t ratio_kind, int32_t anchor_mode, int32_t F, int32_t T,
+                        int32_t *n_out, int32_t *n_keep);
+
+/* Bytes of device workspace wk_compress_chunk needs for this descriptor (0 if it is invalid). */
+size_t wk_compress_workspace_bytes(const wk_compress_desc *desc);
+
+/* World Compression (Sec. 4.3): Eq. 5 redundancy score of every non-anchor key against the
+ * anchor frame's keys, scores pooled over the non-anchor frames, the lowest-scoring n_keep
+ * tokens retained (ties: lower token index first), and the chunk compacted to anchor tokens
+ * followed by the retained tokens in their original order.  K and V are pruned with the same
+ * indices and rows are copied bit for bit.
+ *
+ *   K, V       device, [batch][H][F*T][d]
+ *   K_anchor   device, [batch][H][T][d]; WK_ANCHOR_EXTERNAL only, else must be NULL
+ *   kept_idx   device out, [batch][G][n_out] int32, ascending token indices into the chunk's
+ *              F*T tokens; G = 1 (SHARED) or H (INDEPENDENT).  May be NULL.
+ *   K_out,V_out device out (HBM or pinned+mapped host), [batch][H][n_out][d]
+ *   n_out      host out, stored tokens per chunk (same value wk_keep_count gives). May be NULL.
+ *   workspace  device, at least wk_compress_workspace_bytes(desc) bytes, 256-byte aligned.
+ *              After the call its first batch*G*N_c doubles hold the Eq. 5 scores
+ *              ([batch][G][N_c], N_c = candidates per chunk), which callers may read.
+ * Errors: INVALID_ARG (null/enum), UNSUPPORTED (d != 128; GEMM scoring with fp32),
+ *         RATIO, WORKSPACE. */
+wk_status wk_compress_chunk(const wk_compress_desc *desc, const void *K, const void *V,
+                            const void *K_anchor, int32_t *kept_idx, void *K_out, void *V_out,
+                            int32_t *n_out, void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+#define WK_SCORE_MAX_CHUNKS 4096
+
+/* World Retrieval (Sec. 4.2, Eq. 4) with the camera/action distance of Sec. 5.1: for every
+ * stored chunk the squared L2 distance between translations and the geodesic angle between
+ * rotations (R = R_y(yaw) R_x(pitch), radians), each normalised over the M candidates
+ * (norm_mode) and summed; the min(R, M) chunks of smallest distance are returned in order of
+ * increasing distance (ties: lower chunk id first).  Arithmetic is fp64.
+ *
+ *   poses      device, [M][5] float = (x, y, z, yaw, pitch) of each stored chunk
+ *   cur_pose   host, [5] float, the current camera/action state (read during the call)
+ *   ids_out    device out, [R] int32; entries past n_found are -1
+ *   dist_out   device out, [R] double; entries past n_found are +inf.  May be NULL.
+ *   n_found    device out, int32 = min(R, M)
+ * M = 0 is valid (nothing found).  Errors: INVALID_ARG, UNSUPPORTED (M > WK_SCORE_MAX_CHUNKS). */
+wk_status wk_score_chunks(const float *poses, int32_t M, const float *cur_pose, int32_t norm_mode,
+                          int32_t R, int32_t *ids_out, double *dist_out, int32_t *n_found,
+                          void *hip_stream);
+
+/* Pseudo-poses for keyboard/mouse models (Sec. 5.1): accumulate discrete actions into a
+ * translation and a rotation.  Labels: 0 W forward, 1 A left, 2 S back, 3 D right, 4 yaw-,
+ * 5 yaw+, 6 pitch-, 7 pitch+.  Translation steps of length `step` are taken in the body frame
+ * of the current yaw (forward = (sin yaw, 0, cos yaw), right = (cos yaw, 0, -sin yaw)); rotation
+ * steps are `dangle` radians; pitch is clamped to +-pitch_limit.  poses_out[i] is the state
+ * after label i.  Host function, host pointers.  (The paper gives no step sizes; callers
+ * choose them.)  Errors: INVALID_ARG (null pointer, label outside 0..7). */
+wk_status wk_accumulate_actions(const int32_t *labels, int32_t n, float step, float dangle,
+                                float pitch_limit, float *poses_out /* [n][5] */);
+
+typedef struct wk_store_desc {
+    const void *const *K_ptr; /* device array [M]: address of chunk c's keys, [H][n_tok[c]][d] */
+    const void *const *V_ptr; /* device array [M]: same for values */
+    const int32_t *n_tok;     /* device array [M]: stored tokens of chunk c */
+    int32_t M;                /* chunks in the store */
+    int32_t max_tok;          /* host-known upper bound of n_tok[] */
+    int32_t H, d, dtype;
+} wk_store_desc;
+
+/* Window assembly (Sec. 1 "without re-encoding", Sec. 4.2): window = native rows followed by
+ * the stored rows of each retrieved chunk in the order of ids, byte for byte, for K and V.
+ * The addresses in K_ptr/V_ptr may point to HBM or to pinned+mapped host memory (CPU-offloaded
+ * store, Sec. 7); ids and n_ids come from wk_score_chunks and are read on the device, so no
+ * host synchronisation separates the two calls.
+ *
+ *   ids        device, [R_max] int32; entries < 0 or >= M are skipped
+ *   n_ids      device, int32; only the first min(*n_ids, R_max) ids are used.  NULL = R_max.
+ *   K_native,V_native device, [H][n_native][d]; NULL with n_native > 0 means the native rows
+ *              are already in place in the window and are not copied
+ *   K_win,V_win device out, [H][win_capacity][d]; rows past the assembled length are untouched
+ *   n_win      device out, int32 = n_native + sum of retrieved chunk lengths.  May be NULL.
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, R_max > 1024),
+ *         SHAPE (win_capacity < n_native + R_max * max_tok). */
+wk_status wk_gather_window(const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids,
+                           int32_t R_max, const void *K_native, const void *V_native,
+                           int32_t n_native, void *K_win, void *V_win, int32_t win_capacity,
+                           int32_t *n_win, void *hip_stream);
+
+/* Attention of the denoising chunk's queries over the assembled window (Sec. 4.2, Sec. 4.3):
+ * O = softmax(Q K^T * scale) V per head, every window key visible to every query.
+ * bf16: matrix-core products with fp32 accumulation, probabilities rounded to bf16 before the
+ * P*V product, one rounding of O to bf16 at the end.  fp32: fp32 throughout.
+ *
+ *   Q          device, [H][N_q][d]
+ *   K_win,V_win device, [H][kv_row_stride][d]; the first N_kv rows of each head are attended
+ *   O          device out, [H][N_q][d], same element type as the inputs
+ *   lse        device out, [H][N_q] float: natural-log sum of exp of the scaled logits. May be NULL.
+ *   scale      logit scale; 0 means 1/sqrt(d)
+ *   n_kv_dev   device, int32 or NULL.  If given, min(N_kv, *n_kv_dev) keys are attended (the
+ *              length wk_gather_window wrote), read on the device.  A length of 0 gives O = 0
+ *              and lse = -inf.
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128), SHAPE (N_kv < 1 or N_kv > kv_row_stride). */
+wk_status wk_attention(const void *Q, const void *K_win, const void *V_win, void *O, float *lse,
+                       int32_t H, int32_t N_q, int32_t N_kv, int32_t d, int32_t kv_row_stride,
+                       int32_t dtype, float scale, const int32_t *n_kv_dev, void *hip_stream);
+
+/* Device-visible address of a pinned+mapped host allocation (for K_ptr/V_ptr tables and for
+ * K_out/V_out of wk_compress_chunk).  Errors: INVALID_ARG, HIP (memory is not pinned). */
+wk_status wk_host_device_pointer(void *host_ptr, void **device_ptr);
+
+const char *wk_status_string(wk_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WK_H */

@@ -68,14 +68,21 @@ def keep_count(rho, ratio_kind, anchor_mode, F, T):
     return n_out.value, n_keep.value
 
 
-def compress_scores(K, K_anchor, T, F, head_mode=HEADS_SHARED, anchor_mode=ANCHOR_FIRST_FRAME):
+def compress_scores(K, K_anchor, T, F, head_mode=HEADS_SHARED, anchor_mode=ANCHOR_FIRST_FRAME, cand_sel=None):
+    """Eq. 5 scores [G][N_c]; with cand_sel only those candidate indices are evaluated (others are NaN)."""
     _chk(K)
     H, n_tok, d = K.shape
     assert n_tok == F * T
     n_cand = n_tok if anchor_mode == ANCHOR_EXTERNAL else n_tok - T
     G = H if head_mode == HEADS_INDEPENDENT else 1
     out = np.zeros((G, n_cand), np.float64)
-    rc = lib().wko_compress_scores(_p(K), _p(K_anchor), _code(K), H, d, T, F, head_mode, anchor_mode, _p(out))
+    n_sel = 0
+    if cand_sel is not None:
+        cand_sel = np.ascontiguousarray(cand_sel, np.int32)
+        n_sel = cand_sel.size
+        out[:] = np.nan
+    rc = lib().wko_compress_scores(_p(K), _p(K_anchor), _code(K), H, d, T, F, head_mode, anchor_mode,
+                                   _p(cand_sel), C.c_int64(n_sel), _p(out))
     assert rc == 0, rc
     return out
 

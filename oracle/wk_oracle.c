@@ -99,9 +99,11 @@ int wko_keep_count(double rho, int ratio_kind, int anchor_mode, int F, int T,
  * EXTERNAL:    anchors are K_anchor [H][T][d], candidates all tokens of K.
  * HEADS_SHARED: one score list, the key vector of a token is the
  * concatenation of its H head slices; HEADS_INDEPENDENT: H lists, Eq. 5 per
- * head.  scores is [G][N_c]. */
+ * head.  scores is [G][N_c].  cand_sel (may be NULL) restricts the evaluation to n_sel
+ * candidate indices; the other entries of scores are left untouched. */
 int wko_compress_scores(const void *K, const void *K_anchor, int dtype, int H, int d, int T, int F,
-                        int head_mode, int anchor_mode, double *scores)
+                        int head_mode, int anchor_mode, const int32_t *cand_sel, int64_t n_sel,
+                        double *scores)
 {
     if (!K || !scores || H < 1 || d < 1 || T < 1 || F < 1) return -1;
     if (anchor_mode == WKO_ANCHOR_EXTERNAL && !K_anchor) return -1;
@@ -139,8 +141,11 @@ int wko_compress_scores(const void *K, const void *K_anchor, int dtype, int H, i
             for (int64_t c = 0; c < D; ++c) s += anc[i * D + c] * anc[i * D + c];
             anc_norm[i] = sqrt(s);
         }
+        const int64_t n_eval = cand_sel ? n_sel : n_cand;
 #pragma omp parallel for schedule(static)
-        for (int64_t j = 0; j < n_cand; ++j) {
+        for (int64_t e = 0; e < n_eval; ++e) {
+            const int64_t j = cand_sel ? cand_sel[e] : e;
+            if (j < 0 || j >= n_cand) continue;
             const double *kj = cand + j * D;
             double nj = 0.0;
             for (int64_t c = 0; c < D; ++c) nj += kj[c] * kj[c];
@@ -208,7 +213,7 @@ int wko_compress(const void *K, const void *V, const void *K_anchor, int dtype, 
     const int G = head_mode == WKO_HEADS_INDEPENDENT ? H : 1;
     double *sc = scores_out ? scores_out : (double *)malloc(sizeof(double) * (size_t)G * (n_cand > 0 ? n_cand : 1));
     if (!sc) return -2;
-    int rc = wko_compress_scores(K, K_anchor, dtype, H, d, T, F, head_mode, anchor_mode, sc);
+    int rc = wko_compress_scores(K, K_anchor, dtype, H, d, T, F, head_mode, anchor_mode, NULL, 0, sc);
     if (rc == 0) {
         for (int g = 0; g < G && rc == 0; ++g) {
             int32_t *idx = kept_idx + (size_t)g * n_out;

@@ -1,0 +1,215 @@
+"""Thin Python binding of libwk (include/wk.h): argument marshalling only.
+
+Every function has the name and the meaning of the C entry point it calls; all
+arithmetic happens in the HIP kernels of libwk.so.  PyTorch is used for device
+memory and the current HIP stream.  There is no CPU fallback: if the library is
+missing, importing a function raises.
+"""
+import ctypes as C
+import math
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libwk.so")
+
+WK_OK, WK_ERR_INVALID_ARG, WK_ERR_SHAPE, WK_ERR_RATIO, WK_ERR_WORKSPACE, WK_ERR_UNSUPPORTED, WK_ERR_HIP = range(7)
+WK_F32, WK_BF16 = 0, 1
+WK_HEADS_SHARED, WK_HEADS_INDEPENDENT = 0, 1
+WK_ANCHOR_FIRST_FRAME, WK_ANCHOR_EXTERNAL = 0, 1
+WK_RATIO_CHUNK, WK_RATIO_NONANCHOR = 0, 1
+WK_SCORE_FACTORED, WK_SCORE_GEMM = 0, 1
+WK_NORM_MAX, WK_NORM_MINMAX, WK_NORM_MEAN = 0, 1, 2
+WK_SCORE_MAX_CHUNKS = 4096
+
+EXPORTS = [
+    "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
+    "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_host_device_pointer",
+    "wk_status_string",
+]
+
+
+class WkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (wk_status {status})")
+
+
+class wk_compress_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("H", "d", "T", "F", "batch", "dtype", "head_mode", "anchor_mode", "ratio_kind", "score_algo")]
+    _fields_.append(("rho", C.c_float))
+
+
+class wk_store_desc(C.Structure):
+    _fields_ = [("K_ptr", C.c_void_p), ("V_ptr", C.c_void_p), ("n_tok", C.c_void_p),
+                ("M", C.c_int32), ("max_tok", C.c_int32), ("H", C.c_int32), ("d", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+        L.wk_keep_count.restype = C.c_int
+        L.wk_keep_count.argtypes = [f32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.wk_compress_workspace_bytes.restype = C.c_size_t
+        L.wk_compress_workspace_bytes.argtypes = [C.POINTER(wk_compress_desc)]
+        L.wk_compress_chunk.restype = C.c_int
+        L.wk_compress_chunk.argtypes = [C.POINTER(wk_compress_desc), vp, vp, vp, vp, vp, vp, C.POINTER(i32),
+                                        vp, C.c_size_t, vp]
+        L.wk_score_chunks.restype = C.c_int
+        L.wk_score_chunks.argtypes = [vp, i32, C.POINTER(f32), i32, i32, vp, vp, vp, vp]
+        L.wk_accumulate_actions.restype = C.c_int
+        L.wk_accumulate_actions.argtypes = [vp, i32, f32, f32, f32, vp]
+        L.wk_gather_window.restype = C.c_int
+        L.wk_gather_window.argtypes = [C.POINTER(wk_store_desc), vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, vp]
+        L.wk_attention.restype = C.c_int
+        L.wk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp]
+        L.wk_host_device_pointer.restype = C.c_int
+        L.wk_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
+        L.wk_status_string.restype = C.c_char_p
+        L.wk_status_string.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().wk_status_string(status).decode()
+
+
+def _check(status: int, where: str):
+    if status != WK_OK:
+        raise WkError(status, where)
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return WK_F32
+    if t.dtype == torch.bfloat16:
+        return WK_BF16
+    raise TypeError(f"float32 or bfloat16 expected, got {t.dtype}")
+
+
+def _dev(t, name, dtype=None):
+    """Pointer of a contiguous tensor kernels can address (device, or pinned host)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name}: tensor expected")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: {dtype} expected, got {t.dtype}")
+    if t.is_cuda:
+        return t.data_ptr()
+    if t.is_pinned():
+        return wk_host_device_pointer(t)
+    raise ValueError(f"{name}: must live on the GPU or in pinned host memory")
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def wk_host_device_pointer(t: torch.Tensor) -> int:
+    """wk_host_device_pointer: device-visible address of a pinned host tensor."""
+    out = C.c_void_p()
+    _check(lib().wk_host_device_pointer(t.data_ptr(), C.byref(out)), "wk_host_device_pointer")
+    return out.value
+
+
+def wk_keep_count(rho, ratio_kind, anchor_mode, F, T):
+    """wk_keep_count -> (n_out, n_keep)."""
+    n_out, n_keep = C.c_int32(), C.c_int32()
+    _check(lib().wk_keep_count(rho, ratio_kind, anchor_mode, F, T, C.byref(n_out), C.byref(n_keep)), "wk_keep_count")
+    return n_out.value, n_keep.value
+
+
+def make_compress_desc(H, T, F, dtype, rho, batch=1, d=128, head_mode=WK_HEADS_SHARED,
+                       anchor_mode=WK_ANCHOR_FIRST_FRAME, ratio_kind=WK_RATIO_CHUNK,
+                       score_algo=WK_SCORE_FACTORED) -> wk_compress_desc:
+    return wk_compress_desc(H, d, T, F, batch, dtype, head_mode, anchor_mode, ratio_kind, score_algo, rho)
+
+
+def wk_compress_workspace_bytes(desc: wk_compress_desc) -> int:
+    return lib().wk_compress_workspace_bytes(C.byref(desc))
+
+
+def wk_compress_chunk(desc: wk_compress_desc, K, V, K_anchor, kept_idx, K_out, V_out, workspace) -> int:
+    """wk_compress_chunk.  All tensors are caller-allocated; returns n_out."""
+    n_out = C.c_int32()
+    st = lib().wk_compress_chunk(C.byref(desc), _dev(K, "K"), _dev(V, "V"), _dev(K_anchor, "K_anchor"),
+                                 _dev(kept_idx, "kept_idx", torch.int32), _dev(K_out, "K_out"), _dev(V_out, "V_out"),
+                                 C.byref(n_out), _dev(workspace, "workspace"),
+                                 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "wk_compress_chunk")
+    return n_out.value
+
+
+def wk_score_chunks(poses, M, cur_pose, norm_mode, R, ids_out, dist_out, n_found):
+    """wk_score_chunks.  poses: device float32 [M][5]; cur_pose: 5 host floats."""
+    cur = (C.c_float * 5)(*[float(x) for x in cur_pose])
+    st = lib().wk_score_chunks(_dev(poses, "poses", torch.float32), M, cur, norm_mode, R,
+                               _dev(ids_out, "ids_out", torch.int32), _dev(dist_out, "dist_out", torch.float64),
+                               _dev(n_found, "n_found", torch.int32), _stream())
+    _check(st, "wk_score_chunks")
+
+
+def wk_accumulate_actions(labels, step=1.0, dangle=math.radians(15.0), pitch_limit=math.radians(60.0)):
+    """wk_accumulate_actions (host).  labels: int32 numpy array or CPU tensor -> float32 CPU tensor [n][5]."""
+    lab = torch.as_tensor(labels, dtype=torch.int32).contiguous()
+    out = torch.zeros((lab.numel(), 5), dtype=torch.float32)
+    st = lib().wk_accumulate_actions(lab.data_ptr(), lab.numel(), step, dangle, pitch_limit, out.data_ptr())
+    _check(st, "wk_accumulate_actions")
+    return out
+
+
+class Store:
+    """Device-side tables describing a chunk store (wk_store_desc) built from lists of tensors."""
+
+    def __init__(self, K_chunks, V_chunks, device="cuda"):
+        assert len(K_chunks) == len(V_chunks)
+        self.K_chunks, self.V_chunks = list(K_chunks), list(V_chunks)  # keep the memory alive
+        ref = K_chunks[0]
+        self.H, self.d = ref.shape[0], ref.shape[2]
+        self.dtype = dtype_code(ref)
+        n_tok = [k.shape[1] for k in K_chunks]
+        self.max_tok = max(n_tok)
+        kp = [_dev(k, "K chunk") for k in K_chunks]
+        vp = [_dev(v, "V chunk") for v in V_chunks]
+        self.K_ptr = torch.tensor(kp, dtype=torch.int64, device=device)
+        self.V_ptr = torch.tensor(vp, dtype=torch.int64, device=device)
+        self.n_tok = torch.tensor(n_tok, dtype=torch.int32, device=device)
+        self.desc = wk_store_desc(self.K_ptr.data_ptr(), self.V_ptr.data_ptr(), self.n_tok.data_ptr(),
+                                  len(K_chunks), self.max_tok, self.H, self.d, self.dtype)
+
+
+def wk_gather_window(store_desc: wk_store_desc, ids, n_ids, R_max, K_native, V_native, n_native, K_win, V_win,
+                  win_capacity, n_win):
+    """wk_gather_window."""
+    st = lib().wk_gather_window(C.byref(store_desc), _dev(ids, "ids", torch.int32),
+                                _dev(n_ids, "n_ids", torch.int32), R_max, _dev(K_native, "K_native"),
+                                _dev(V_native, "V_native"), n_native, _dev(K_win, "K_win"), _dev(V_win, "V_win"),
+                                win_capacity, _dev(n_win, "n_win", torch.int32), _stream())
+    _check(st, "wk_gather_window")
+
+
+def wk_attention(Q, K_win, V_win, O, lse=None, N_kv=None, scale=0.0, n_kv_dev=None):
+    """wk_attention.  Q [H][N_q][d]; K_win/V_win [H][stride][d]; O like Q (written in place)."""
+    H, N_q, d = Q.shape
+    stride = K_win.shape[1]
+    N_kv = stride if N_kv is None else N_kv
+    st = lib().wk_attention(_dev(Q, "Q"), _dev(K_win, "K_win", Q.dtype), _dev(V_win, "V_win", Q.dtype),
+                            _dev(O, "O", Q.dtype), _dev(lse, "lse", torch.float32), H, N_q, N_kv, d, stride,
+                            dtype_code(Q), scale, _dev(n_kv_dev, "n_kv_dev", torch.int32), _stream())
+    _check(st, "wk_attention")
+    return O

@@ -1,0 +1,380 @@
+// World Compression (paper Sec. 4.3, Eq. 5): redundancy scores, pooled bottom-P% selection,
+// chunk compaction.  Kernels for gfx950; every pass is a coalesced stream over K (or K and V),
+// 16 lanes x 16 bytes per bf16 row, bound by HBM bandwidth.
+//
+// Factored evaluation of Eq. 5: cos is bilinear in the normalised vectors, so
+//   s_j = (1/T) sum_i khat_j . khat_i = khat_j . m,   m = (1/T) sum_i khat_i.
+// The pass structure is: squared norms of the anchor tokens -> m -> one pass over the
+// candidates that accumulates both k_j . m and |k_j|^2.  Partial sums over a lane's 8 elements
+// are fp32 (bf16 products are exact in fp32), everything across lanes and heads is fp64, so the
+// scores agree with an fp64 evaluation of the double sum to ~1e-9 absolute.
+#include <cmath>
+
+#include "wk_internal.h"
+
+namespace {
+
+using wk::kRowLanes;
+using wk::load_row8;
+
+constexpr int kRowsPerBlock = 16;  // 256 threads
+
+struct CompressDims {
+    int H, T, n_tok;    // heads, anchors per chunk, rows per head in K
+    int first_cand;     // first candidate row in K (T, or 0 with an external anchor)
+    int n_cand;         // candidate rows
+    int G, hg;          // score lists per chunk, heads per list
+    int a_rows;         // rows per head in the anchor buffer
+    int n_keep, n_out;
+};
+
+// nsq[(b*G+g)*T + i] = |anchor key i|^2 over the heads of group g
+template <int DT>
+__global__ __launch_bounds__(256) void k_anchor_normsq(const char *__restrict__ A, CompressDims p,
+                                                       double *__restrict__ nsq) {
+    const int i = blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const int sub = threadIdx.x % kRowLanes;
+    const int g = blockIdx.y, b = blockIdx.z;
+    if (i >= p.T) return;
+    const size_t row_bytes = WK_D * wk::esize(DT);
+    double acc = 0.0;
+    for (int hh = 0; hh < p.hg; ++hh) {
+        const int h = p.G == 1 ? hh : g;
+        const char *row = A + (((size_t)b * p.H + h) * p.a_rows + i) * row_bytes;
+        float v[8];
+        load_row8<DT>(row, sub, v);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf(v[e], v[e], s);
+        acc += (double)s;
+    }
+    acc = wk::row_group_sum(acc);
+    if (sub == 0) nsq[((size_t)b * p.G + g) * p.T + i] = acc;
+}
+
+// m[(b*H+h)*128 + c] = (1/T) sum_i A[b][h][i][c] / |anchor key i|   (fp32 result of an fp64 sum)
+template <int DT>
+__global__ __launch_bounds__(256) void k_anchor_mean(const char *__restrict__ A, CompressDims p,
+                                                     const double *__restrict__ nsq,
+                                                     float *__restrict__ m) {
+    __shared__ double red[kRowsPerBlock][WK_D];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int g = p.G == 1 ? 0 : h;
+    const int slot = threadIdx.x / kRowLanes, sub = threadIdx.x % kRowLanes;
+    const size_t row_bytes = WK_D * wk::esize(DT);
+    const char *base = A + ((size_t)b * p.H + h) * p.a_rows * row_bytes;
+    const double *nq = nsq + ((size_t)b * p.G + g) * p.T;
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = slot; i < p.T; i += kRowsPerBlock) {
+        float v[8];
+        load_row8<DT>(base + (size_t)i * row_bytes, sub, v);
+        const double n2 = nq[i];
+        const double rn = n2 < 1e-60 ? 0.0 : 1.0 / sqrt(n2);  // zero-norm key: its cosines are 0
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (double)v[e] * rn;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[slot][sub * 8 + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < WK_D) {
+        double s = 0.0;
+#pragma unroll
+        for (int r = 0; r < kRowsPerBlock; ++r) s += red[r][threadIdx.x];
+        m[((size_t)b * p.H + h) * WK_D + threadIdx.x] = (float)(s / (double)p.T);
+    }
+}
+
+// scores[(b*G+g)*n_cand + j] = (k_j . m) / |k_j|
+template <int DT>
+__global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__ K, CompressDims p,
+                                                        const float *__restrict__ m,
+                                                        double *__restrict__ scores) {
+    const int j = blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const int sub = threadIdx.x % kRowLanes;
+    const int g = blockIdx.y, b = blockIdx.z;
+    if (j >= p.n_cand) return;
+    const size_t row_bytes = WK_D * wk::esize(DT);
+    double dacc = 0.0, nacc = 0.0;
+    for (int hh = 0; hh < p.hg; ++hh) {
+        const int h = p.G == 1 ? hh : g;
+        const char *row = K + (((size_t)b * p.H + h) * p.n_tok + p.first_cand + j) * row_bytes;
+        float v[8];
+        load_row8<DT>(row, sub, v);
+        const float4 *mp = reinterpret_cast<const float4 *>(m + ((size_t)b * p.H + h) * WK_D) + 2 * sub;
+        const float4 m0 = mp[0], m1 = mp[1];
+        const float mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+        float dp = 0.f, ns = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            dp = fmaf(v[e], mm[e], dp);
+            ns = fmaf(v[e], v[e], ns);
+        }
+        dacc += (double)dp;
+        nacc += (double)ns;
+    }
+    dacc = wk::row_group_sum(dacc);
+    nacc = wk::row_group_sum(nacc);
+    if (sub == 0) {
+        double s = nacc < 1e-60 ? 0.0 : dacc / sqrt(nacc);
+        scores[((size_t)b * p.G + g) * p.n_cand + j] = s + 0.0;  // -0.0 -> +0.0
+    }
+}
+
+// ---- selection: n_keep lowest scores of one list, ties to the lower index -------------------
+
+__device__ inline uint64_t order_key(double s) {
+    const uint64_t u = (uint64_t)__double_as_longlong(s);
+    return (u >> 63) ? ~u : (u | 0x8000000000000000ull);  // unsigned order == numeric order
+}
+
+constexpr int kSelThreads = 1024;
+
+// exclusive scan of one int per thread over the block; total = sum over the block
+__device__ inline int block_excl_scan(int v, int *wsum /*[kSelThreads/64]*/, int &total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(x, o);
+        if (lane >= o) x += y;
+    }
+    __syncthreads();  // wsum may still be read from the previous scan
+    if (lane == 63) wsum[w] = x;
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kSelThreads / 64; ++i) {
+        const int t = wsum[i];
+        if (i < w) off += t;
+        tot += t;
+    }
+    total = tot;
+    return off + x - v;
+}
+
+// One block per list.  Radix-select (8 passes of 8 bits over order-preserving 64-bit keys) finds
+// the n_keep-th smallest score tau; then tokens with score < tau, plus the first few (by index)
+// with score == tau, are written in ascending index order via block scans.
+__global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict__ scores,
+                                                        CompressDims p, int32_t *__restrict__ kept_idx) {
+    __shared__ unsigned hist[256];
+    __shared__ uint64_t s_prefix;
+    __shared__ int s_k;
+    __shared__ int wsum[kSelThreads / 64];
+    const int list = blockIdx.x;  // b*G + g
+    const double *s = scores + (size_t)list * p.n_cand;
+    int32_t *out = kept_idx + (size_t)list * p.n_out;
+    const int n = p.n_cand, tid = threadIdx.x;
+
+    for (int i = tid; i < p.first_cand; i += kSelThreads) out[i] = i;  // anchor tokens, kept in full
+    if (p.n_keep == 0) return;
+
+    uint64_t prefix = 0;
+    int k = p.n_keep;  // rank (1-based) still to locate among keys matching the prefix
+    if (p.n_keep < n) {
+        for (int pass = 7; pass >= 0; --pass) {
+            const int shift = pass * 8;
+            const uint64_t himask = pass == 7 ? 0ull : (~0ull << (shift + 8));
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int j = tid; j < n; j += kSelThreads) {
+                const uint64_t key = order_key(s[j]);
+                if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int cum = 0, bucket = 255;
+                for (int bkt = 0; bkt < 256; ++bkt) {
+                    const int c = (int)hist[bkt];
+                    if (cum + c >= k) { bucket = bkt; break; }
+                    cum += c;
+                }
+                s_k = k - cum;
+                s_prefix = prefix | ((uint64_t)bucket << shift);
+            }
+            __syncthreads();
+            k = s_k;
+            prefix = s_prefix;
+        }
+    } else {
+        prefix = ~0ull;  // keep everything: every key is below (or equal to) the largest key
+        k = n;
+    }
+    // prefix = tau, k = how many of the keys equal to tau are kept (lowest indices first)
+    int eq_base = 0, out_base = 0;
+    for (int j0 = 0; j0 < n; j0 += kSelThreads) {
+        const int j = j0 + tid;
+        uint64_t key = 0;
+        bool less = false, eq = false;
+        if (j < n) {
+            key = order_key(s[j]);
+            less = key < prefix;
+            eq = key == prefix;
+        }
+        int eq_tot, keep_tot;
+        const int eq_rank = eq_base + block_excl_scan(eq ? 1 : 0, wsum, eq_tot);
+        const bool keep = less || (eq && eq_rank < k);
+        const int pos = out_base + block_excl_scan(keep ? 1 : 0, wsum, keep_tot);
+        if (keep && pos < p.n_keep) out[p.first_cand + pos] = p.first_cand + j;
+        eq_base += eq_tot;
+        out_base += keep_tot;
+    }
+}
+
+// K_out/V_out[b][h][r] = K/V[b][h][kept_idx[b][g(h)][r]], rows copied verbatim
+template <int DT>
+__global__ __launch_bounds__(256) void k_compact(const char *__restrict__ K, const char *__restrict__ V,
+                                                 CompressDims p, const int32_t *__restrict__ kept_idx,
+                                                 char *__restrict__ K_out, char *__restrict__ V_out) {
+    const int r = blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const int sub = threadIdx.x % kRowLanes;
+    const int h = blockIdx.y, b = blockIdx.z;
+    if (r >= p.n_out) return;
+    const int g = p.G == 1 ? 0 : h;
+    const int src = kept_idx[((size_t)b * p.G + g) * p.n_out + r];
+    constexpr size_t row_bytes = WK_D * (DT == WK_BF16 ? 2 : 4);
+    constexpr int vec_per_lane = row_bytes / (kRowLanes * 16);  // 1 (bf16) or 2 (fp32)
+    const size_t in_off = (((size_t)b * p.H + h) * p.n_tok + src) * row_bytes;
+    const size_t out_off = (((size_t)b * p.H + h) * p.n_out + r) * row_bytes;
+#pragma unroll
+    for (int t = 0; t < vec_per_lane; ++t) {
+        const int c = sub + t * kRowLanes;
+        const uint4 kv = reinterpret_cast<const uint4 *>(K + in_off)[c];
+        const uint4 vv = reinterpret_cast<const uint4 *>(V + in_off)[c];
+        reinterpret_cast<uint4 *>(K_out + out_off)[c] = kv;
+        reinterpret_cast<uint4 *>(V_out + out_off)[c] = vv;
+    }
+}
+
+struct WsLayout {
+    size_t scores, nsq, mean, kept, total;
+};
+
+bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
+    if (!d || d->H < 1 || d->T < 1 || d->F < 1 || d->batch < 1) return false;
+    int32_t n_out = 0, n_keep = 0;
+    if (wk_keep_count(d->rho, d->ratio_kind, d->anchor_mode, d->F, d->T, &n_out, &n_keep) != WK_OK)
+        return false;
+    const bool ext = d->anchor_mode == WK_ANCHOR_EXTERNAL;
+    p.H = d->H;
+    p.T = d->T;
+    p.n_tok = d->F * d->T;
+    p.first_cand = ext ? 0 : d->T;
+    p.n_cand = p.n_tok - p.first_cand;
+    p.G = d->head_mode == WK_HEADS_INDEPENDENT ? d->H : 1;
+    p.hg = d->head_mode == WK_HEADS_INDEPENDENT ? 1 : d->H;
+    p.a_rows = ext ? d->T : p.n_tok;
+    p.n_keep = n_keep;
+    p.n_out = n_out;
+    const size_t lists = (size_t)d->batch * p.G;
+    size_t off = 0;
+    ws.scores = off; off = wk::align_up(off + lists * (size_t)(p.n_cand > 0 ? p.n_cand : 1) * sizeof(double), 256);
+    ws.nsq = off;    off = wk::align_up(off + lists * (size_t)p.T * sizeof(double), 256);
+    ws.mean = off;   off = wk::align_up(off + (size_t)d->batch * d->H * WK_D * sizeof(float), 256);
+    ws.kept = off;   off = wk::align_up(off + lists * (size_t)n_out * sizeof(int32_t), 256);
+    ws.total = off;
+    return true;
+}
+
+wk_status check_desc(const wk_compress_desc *d) {
+    if (!d) return WK_ERR_INVALID_ARG;
+    if (d->H < 1 || d->T < 1 || d->F < 1 || d->batch < 1 || d->d < 1) return WK_ERR_INVALID_ARG;
+    if (d->dtype != WK_F32 && d->dtype != WK_BF16) return WK_ERR_INVALID_ARG;
+    if (d->head_mode != WK_HEADS_SHARED && d->head_mode != WK_HEADS_INDEPENDENT) return WK_ERR_INVALID_ARG;
+    if (d->anchor_mode != WK_ANCHOR_FIRST_FRAME && d->anchor_mode != WK_ANCHOR_EXTERNAL) return WK_ERR_INVALID_ARG;
+    if (d->ratio_kind != WK_RATIO_CHUNK && d->ratio_kind != WK_RATIO_NONANCHOR) return WK_ERR_INVALID_ARG;
+    if (d->score_algo != WK_SCORE_FACTORED && d->score_algo != WK_SCORE_GEMM) return WK_ERR_INVALID_ARG;
+    if (d->d != WK_D) return WK_ERR_UNSUPPORTED;
+    if (d->score_algo == WK_SCORE_GEMM) return WK_ERR_UNSUPPORTED;
+    if ((int64_t)d->F * d->T > (1 << 24)) return WK_ERR_UNSUPPORTED;
+    return WK_OK;
+}
+
+template <int DT>
+wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsLayout &ws, const void *K,
+                     const void *V, const void *K_anchor, int32_t *kept_idx, void *K_out, void *V_out,
+                     char *wsp, hipStream_t st) {
+    double *scores = reinterpret_cast<double *>(wsp + ws.scores);
+    double *nsq = reinterpret_cast<double *>(wsp + ws.nsq);
+    float *mean = reinterpret_cast<float *>(wsp + ws.mean);
+    int32_t *kept = kept_idx ? kept_idx : reinterpret_cast<int32_t *>(wsp + ws.kept);
+    const char *A = reinterpret_cast<const char *>(d->anchor_mode == WK_ANCHOR_EXTERNAL ? K_anchor : K);
+    const char *Kc = reinterpret_cast<const char *>(K);
+    if (p.n_cand > 0) {  // scores are always produced: callers may read them from the workspace
+        dim3 g1((p.T + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
+        hipLaunchKernelGGL(k_anchor_normsq<DT>, g1, dim3(256), 0, st, A, p, nsq);
+        WK_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_anchor_mean<DT>, dim3(p.H, d->batch), dim3(256), 0, st, A, p, nsq, mean);
+        WK_LAUNCH_CHECK();
+        dim3 g3((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
+        hipLaunchKernelGGL(k_score_factored<DT>, g3, dim3(256), 0, st, Kc, p, mean, scores);
+        WK_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_select, dim3(d->batch * p.G), dim3(kSelThreads), 0, st, scores, p, kept);
+    WK_LAUNCH_CHECK();
+    dim3 g5((p.n_out + kRowsPerBlock - 1) / kRowsPerBlock, p.H, d->batch);
+    hipLaunchKernelGGL(k_compact<DT>, g5, dim3(256), 0, st, Kc, reinterpret_cast<const char *>(V), p, kept,
+                       reinterpret_cast<char *>(K_out), reinterpret_cast<char *>(V_out));
+    WK_LAUNCH_CHECK();
+    return WK_OK;
+}
+
+}  // namespace
+
+extern "C" wk_status wk_keep_count(float rho, int32_t ratio_kind, int32_t anchor_mode, int32_t F, int32_t T,
+                                   int32_t *n_out, int32_t *n_keep) {
+    if (F < 1 || T < 1) return WK_ERR_INVALID_ARG;
+    if (ratio_kind != WK_RATIO_CHUNK && ratio_kind != WK_RATIO_NONANCHOR) return WK_ERR_INVALID_ARG;
+    if (anchor_mode != WK_ANCHOR_FIRST_FRAME && anchor_mode != WK_ANCHOR_EXTERNAL) return WK_ERR_INVALID_ARG;
+    if (!(rho >= 0.f) || !(rho <= 1.f)) return WK_ERR_RATIO;
+    const int64_t n_anchor = anchor_mode == WK_ANCHOR_EXTERNAL ? 0 : T;
+    const int64_t n_tok = (int64_t)F * T, n_cand = n_tok - n_anchor;
+    // half away from zero, in double (a float rho is exactly representable in double)
+    auto round_half_away = [](double x) { return (int64_t)llround(x); };
+    int64_t keep, out;
+    if (ratio_kind == WK_RATIO_CHUNK) {
+        out = round_half_away((double)rho * (double)n_tok);
+        keep = out - n_anchor;
+    } else {
+        keep = round_half_away((double)rho * (double)n_cand);
+        out = keep + n_anchor;
+    }
+    if (keep < 0 || keep > n_cand || out < 1 || out > INT32_MAX) return WK_ERR_RATIO;
+    if (n_out) *n_out = (int32_t)out;
+    if (n_keep) *n_keep = (int32_t)keep;
+    return WK_OK;
+}
+
+extern "C" size_t wk_compress_workspace_bytes(const wk_compress_desc *desc) {
+    CompressDims p;
+    WsLayout ws;
+    if (check_desc(desc) != WK_OK || !make_dims(desc, p, ws)) return 0;
+    return ws.total;
+}
+
+extern "C" wk_status wk_compress_chunk(const wk_compress_desc *desc, const void *K, const void *V,
+                                       const void *K_anchor, int32_t *kept_idx, void *K_out, void *V_out,
+                                       int32_t *n_out, void *workspace, size_t workspace_bytes,
+                                       void *hip_stream) {
+    wk_status st = check_desc(desc);
+    if (st != WK_OK) return st;
+    if (!K || !V || !K_out || !V_out) return WK_ERR_INVALID_ARG;
+    const bool ext = desc->anchor_mode == WK_ANCHOR_EXTERNAL;
+    if (ext != (K_anchor != nullptr)) return WK_ERR_INVALID_ARG;
+    int32_t no = 0, nk = 0;
+    st = wk_keep_count(desc->rho, desc->ratio_kind, desc->anchor_mode, desc->F, desc->T, &no, &nk);
+    if (st != WK_OK) return st;
+    CompressDims p;
+    WsLayout ws;
+    if (!make_dims(desc, p, ws)) return WK_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < ws.total) return WK_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WK_ERR_WORKSPACE;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    char *wsp = reinterpret_cast<char *>(workspace);
+    if (desc->dtype == WK_BF16)
+        st = launch_all<WK_BF16>(desc, p, ws, K, V, K_anchor, kept_idx, K_out, V_out, wsp, stream);
+    else
+        st = launch_all<WK_F32>(desc, p, ws, K, V, K_anchor, kept_idx, K_out, V_out, wsp, stream);
+    if (st == WK_OK && n_out) *n_out = no;
+    return st;
+}

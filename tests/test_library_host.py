@@ -1,0 +1,122 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+rejects bad arguments before launching anything, and its host-side helpers agree with the oracle."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2605_22718_amd as wk
+import wk_synth as ws
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "wk.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(wk_[a-z_]+)\s*\(", header))
+    assert declared == set(wk.EXPORTS), declared ^ set(wk.EXPORTS)
+    L = wk.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    seen = {wk.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def test_keep_count_matches_oracle_and_paper_counts():
+    for T in (880, 1560, 7, 1):
+        for F in (1, 2, 3, 4):
+            for kind in (wk.WK_RATIO_CHUNK, wk.WK_RATIO_NONANCHOR):
+                for anchor in (wk.WK_ANCHOR_FIRST_FRAME, wk.WK_ANCHOR_EXTERNAL):
+                    for rho in (0.0, 0.125, 0.25, 0.3, 0.5, 0.75, 1.0):
+                        rho32 = float(np.float32(rho))
+                        try:
+                            expect = oracle.keep_count(rho32, kind, anchor, F, T)
+                        except ValueError:
+                            with pytest.raises(wk.WkError) as e:
+                                wk.wk_keep_count(rho32, kind, anchor, F, T)
+                            assert e.value.status == wk.WK_ERR_RATIO
+                            continue
+                        assert wk.wk_keep_count(rho32, kind, anchor, F, T) == expect
+    assert wk.wk_keep_count(0.25, wk.WK_RATIO_NONANCHOR, wk.WK_ANCHOR_FIRST_FRAME, 3, 880) == (1320, 440)
+    assert wk.wk_keep_count(0.5, wk.WK_RATIO_CHUNK, wk.WK_ANCHOR_FIRST_FRAME, 3, 1560) == (2340, 780)
+    with pytest.raises(wk.WkError):
+        wk.wk_keep_count(1.01, wk.WK_RATIO_CHUNK, wk.WK_ANCHOR_FIRST_FRAME, 3, 880)
+    with pytest.raises(wk.WkError):
+        wk.wk_keep_count(float("nan"), wk.WK_RATIO_CHUNK, wk.WK_ANCHOR_FIRST_FRAME, 3, 880)
+
+
+def test_accumulate_actions_matches_oracle():
+    step, dangle, lim = (float(np.float32(x)) for x in (1.0, math.radians(15.0), math.radians(60.0)))
+    for n, seed in [(0, 1), (1, 2), (50, 3), (1000, 4)]:
+        labels = ws.make_action_labels(n, seed)
+        got = wk.wk_accumulate_actions(labels, step, dangle, lim).numpy()
+        ref = oracle.accumulate_actions(labels, step, dangle, lim)
+        np.testing.assert_array_equal(got, ref)
+    with pytest.raises(wk.WkError) as e:
+        wk.wk_accumulate_actions(np.array([0, 9], np.int32))
+    assert e.value.status == wk.WK_ERR_INVALID_ARG
+
+
+def test_workspace_size_and_descriptor_validation():
+    d = wk.make_compress_desc(12, 880, 3, wk.WK_BF16, 0.5)
+    n = wk.wk_compress_workspace_bytes(d)
+    assert n >= 1760 * 8 + 880 * 8 + 12 * 128 * 4 and n % 256 == 0
+    bad = wk.make_compress_desc(12, 880, 3, wk.WK_BF16, 0.5, d=64)
+    assert wk.wk_compress_workspace_bytes(bad) == 0
+    L = wk.lib()
+    one = C.c_void_p(256)   # never dereferenced: every call below fails validation first
+    n_out = C.c_int32(-7)
+    assert L.wk_compress_chunk(C.byref(bad), one, one, None, None, one, one, C.byref(n_out), one, 1 << 30, None) \
+        == wk.WK_ERR_UNSUPPORTED
+    assert L.wk_compress_chunk(C.byref(d), None, one, None, None, one, one, C.byref(n_out), one, 1 << 30, None) \
+        == wk.WK_ERR_INVALID_ARG
+    assert L.wk_compress_chunk(C.byref(d), one, one, None, None, one, one, C.byref(n_out), one, 16, None) \
+        == wk.WK_ERR_WORKSPACE
+    assert L.wk_compress_chunk(C.byref(d), one, one, None, None, one, one, C.byref(n_out), C.c_void_p(8), 1 << 30, None) \
+        == wk.WK_ERR_WORKSPACE      # misaligned
+    assert L.wk_compress_chunk(C.byref(d), one, one, one, None, one, one, C.byref(n_out), one, 1 << 30, None) \
+        == wk.WK_ERR_INVALID_ARG    # anchor given in first-frame mode
+    low = wk.make_compress_desc(40, 1560, 3, wk.WK_BF16, 0.25)   # below the anchor frame
+    assert L.wk_compress_chunk(C.byref(low), one, one, None, None, one, one, C.byref(n_out), one, 1 << 30, None) \
+        == wk.WK_ERR_RATIO
+    assert n_out.value == -7    # outputs untouched on error
+
+
+def test_argument_validation_of_the_other_calls():
+    L = wk.lib()
+    one = C.c_void_p(256)
+    cur = (C.c_float * 5)()
+    assert L.wk_score_chunks(one, -1, cur, 0, 1, one, None, one, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_score_chunks(one, 5, cur, 7, 1, one, None, one, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_score_chunks(one, 5, cur, 0, 1, one, None, None, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_score_chunks(one, wk.WK_SCORE_MAX_CHUNKS + 1, cur, 0, 1, one, None, one, None) == wk.WK_ERR_UNSUPPORTED
+    # attention
+    args = dict(H=2, N_q=8, N_kv=8, d=128, stride=8, dtype=wk.WK_BF16)
+    def attn(**kw):
+        a = dict(args, **kw)
+        return L.wk_attention(one, one, one, one, None, a["H"], a["N_q"], a["N_kv"], a["d"], a["stride"],
+                              a["dtype"], 0.0, None, None)
+    assert attn(d=64) == wk.WK_ERR_UNSUPPORTED
+    assert attn(N_kv=0) == wk.WK_ERR_SHAPE
+    assert attn(N_kv=9) == wk.WK_ERR_SHAPE
+    assert attn(dtype=5) == wk.WK_ERR_INVALID_ARG
+    assert attn(H=0) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_attention(None, one, one, one, None, 2, 8, 8, 128, 8, 1, 0.0, None, None) == wk.WK_ERR_INVALID_ARG
+    # gather
+    sd = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 128, wk.WK_BF16)
+    assert L.wk_gather_window(C.byref(sd), one, None, 2, one, one, 5, one, one, 24, None, None) == wk.WK_ERR_SHAPE
+    assert L.wk_gather_window(C.byref(sd), None, None, 2, one, one, 5, one, one, 25, None, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_gather_window(C.byref(sd), one, None, 2, one, None, 5, one, one, 25, None, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_gather_window(C.byref(sd), one, None, 2000, one, one, 5, one, one, 1 << 30, None, None) \
+        == wk.WK_ERR_UNSUPPORTED
+    sd64 = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 64, wk.WK_BF16)
+    assert L.wk_gather_window(C.byref(sd64), one, None, 2, one, one, 5, one, one, 25, None, None) == wk.WK_ERR_UNSUPPORTED
+    assert L.wk_host_device_pointer(None, None) == wk.WK_ERR_INVALID_ARG
