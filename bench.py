@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the WorldKV hot path on one MI355X.
+
+A step = one pass of the whole path for one transformer layer and one denoising step on the
+LingBot-World-Fast-shaped workload (40 heads, d = 128, 1,560 tokens/frame): compress one evicted
+3-frame chunk (wk_compress_chunk), score the 120-chunk store and pick R = 8 (wk_score_chunks),
+assemble the 28,080-key window (wk_gather_window) and attend 4,680 queries over it (wk_attention).
+All inputs are seeded synthetic tensors already resident in HBM when the timed region starts.
+
+Prints one JSON line.  `value` is attention FLOP per step (4*N_q*N_kv*d*H) divided by the time of
+the whole step; the attention kernel alone is in `roofline` (HIP events around that kernel).
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+import paper_2605_22718_amd as wk
+import wk_synth as ws
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload index (1 Matrix-Game, 2 LingBot)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pinned", action="store_true", help="skip the pinned-host store measurement")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def build_store(cfg, dev, n_out):
+    """Fill the store by compressing M seeded chunks on the GPU (wk_compress_chunk)."""
+    dt = ws.torch_dtype(cfg.dtype)
+    desc = wk.make_compress_desc(cfg.H, cfg.T, cfg.F, cfg.dtype, cfg.rho, ratio_kind=cfg.ratio_kind,
+                                 anchor_mode=cfg.anchor_mode, head_mode=cfg.head_mode)
+    wsb = torch.empty(wk.wk_compress_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    store_k = torch.empty((cfg.M, cfg.H, n_out, cfg.d), dtype=dt, device=dev)
+    store_v = torch.empty_like(store_k)
+    for c in range(cfg.M):
+        K, V, A = ws.make_chunk(cfg, c, dev)
+        wk.wk_compress_chunk(desc, K, V, A, None, store_k[c], store_v[c], wsb)
+    torch.cuda.synchronize()
+    return desc, wsb, store_k, store_v
+
+
+def cpu_baseline(cfg, Q, Kw, Vw, N_kv, raw_chunk, poses, cur, n_out, target_s):
+    """Time the fp64 oracle on a bounded sample of the same workload and extrapolate each call to
+    its full size.  The oracle is the baseline as written, never tuned."""
+    import oracle
+
+    H, N_q = cfg.H, cfg.N_q
+    Qc, Kc, Vc = Q.cpu(), Kw.cpu(), Vw.cpu()
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(N_q, 4, replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.attention(Qc, Kc, Vc, N_kv=N_kv, rows=rows)
+    t_probe = time.perf_counter() - t0
+    n_rows = int(max(4, min(N_q, 0.7 * target_s / (t_probe / 4))))
+    rows = np.sort(rng.choice(N_q, n_rows, replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.attention(Qc, Kc, Vc, N_kv=N_kv, rows=rows)
+    t_att = time.perf_counter() - t0
+    att_full = t_att * N_q / n_rows
+    # compress: Eq. 5 double loop on a sample of candidates
+    Kr = raw_chunk[0].cpu()
+    n_cand = (cfg.F - 1) * cfg.T
+    sel = np.sort(rng.choice(n_cand, 16, replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.compress_scores(Kr, None, cfg.T, cfg.F, cfg.head_mode, cfg.anchor_mode, cand_sel=sel)
+    t_c = time.perf_counter() - t0
+    comp_full = t_c * n_cand / sel.size
+    t0 = time.perf_counter()
+    oracle.score_chunks(poses, cur, cfg.R)
+    t_s = time.perf_counter() - t0
+    # gather: one head's share of the window, copied by the oracle
+    t0 = time.perf_counter()
+    Kc[:1].clone(), Vc[:1].clone()
+    t_g = (time.perf_counter() - t0) * H
+    step = att_full + comp_full + t_s + t_g
+    flops = 4.0 * N_q * N_kv * cfg.d * H
+    return {
+        "value": flops / step / 1e12, "unit": "TFLOP/s", "cores": oracle.n_threads(), "kind": "oracle",
+        "sample": f"fp64 oracle: attention on {n_rows} of {N_q} query rows x {H} heads, Eq.5 scores on "
+                  f"{sel.size} of {n_cand} candidates, retrieval in full, one head's window copy; each "
+                  f"extrapolated to the full step",
+        "attention_only_tflops": flops / att_full / 1e12,
+        "extrapolated_ms": {"attention": att_full * 1e3, "compress": comp_full * 1e3, "score": t_s * 1e3,
+                            "gather": t_g * 1e3},
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path shards by heads with no exchange; "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = ws.get_config(a.config)
+    dt = ws.torch_dtype(cfg.dtype)
+    n_out, _ = wk.wk_keep_count(cfg.rho, cfg.ratio_kind, cfg.anchor_mode, cfg.F, cfg.T)
+    N_kv = cfg.n_native + cfg.R * n_out
+
+    desc, wsb, store_k, store_v = build_store(cfg, dev, n_out)
+    store = wk.Store([store_k[c] for c in range(cfg.M)], [store_v[c] for c in range(cfg.M)])
+    poses_np, cur = ws.make_poses(cfg.M, cfg.seed)
+    poses = torch.from_numpy(poses_np).to(dev)
+    Q = ws.make_queries(cfg, dev)
+    Kn, Vn = ws.make_native(cfg, dev)
+    evicted = ws.make_chunk(cfg, cfg.M, dev)          # the chunk leaving the window in this step
+    ev_k = torch.empty((cfg.H, n_out, cfg.d), dtype=dt, device=dev)
+    ev_v = torch.empty_like(ev_k)
+    ev_idx = torch.empty((1, n_out), dtype=torch.int32, device=dev)
+    ids = torch.empty(cfg.R, dtype=torch.int32, device=dev)
+    dist = torch.empty(cfg.R, dtype=torch.float64, device=dev)
+    n_found = torch.empty(1, dtype=torch.int32, device=dev)
+    Kw = torch.zeros((cfg.H, N_kv, cfg.d), dtype=dt, device=dev)
+    Vw = torch.zeros_like(Kw)
+    n_win = torch.empty(1, dtype=torch.int32, device=dev)
+    O = torch.empty_like(Q)
+
+    def step(store_desc, ev_att=None):
+        wk.wk_compress_chunk(desc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k, ev_v, wsb)
+        wk.wk_score_chunks(poses, cfg.M, cur, wk.WK_NORM_MAX, cfg.R, ids, dist, n_found)
+        wk.wk_gather_window(store_desc, ids, n_found, cfg.R, Kn, Vn, cfg.n_native, Kw, Vw, N_kv, n_win)
+        if ev_att:
+            ev_att[0].record()
+        wk.wk_attention(Q, Kw, Vw, O, None, N_kv=N_kv, n_kv_dev=n_win)
+        if ev_att:
+            ev_att[1].record()
+
+    for _ in range(a.warmup):
+        step(store.desc)
+    torch.cuda.synchronize()
+    assert int(n_win.item()) == N_kv and int(n_found.item()) == cfg.R
+
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(store.desc, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_step = elapsed / a.steps * 1e3
+    att_ms = float(np.mean([s.elapsed_time(e) for s, e in events]))
+    flops = 4.0 * cfg.N_q * N_kv * cfg.d * cfg.H
+    att_tflops = flops / (att_ms * 1e-3) / 1e12
+
+    # per-call times (each call alone on the stream, HIP events, mean of `steps` repetitions)
+    def time_call(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(reps):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / reps
+
+    reps = max(3, a.steps)
+    per_call = {
+        "compress": time_call(lambda: wk.wk_compress_chunk(desc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k,
+                                                           ev_v, wsb), reps),
+        "score": time_call(lambda: wk.wk_score_chunks(poses, cfg.M, cur, wk.WK_NORM_MAX, cfg.R, ids, dist, n_found),
+                           reps),
+        "gather_hbm": time_call(lambda: wk.wk_gather_window(store.desc, ids, n_found, cfg.R, Kn, Vn, cfg.n_native,
+                                                            Kw, Vw, N_kv, n_win), reps),
+        "attention": att_ms,
+    }
+    row_bytes = cfg.d * Q.element_size()
+    gather_bytes = 2 * 2 * cfg.H * N_kv * row_bytes          # K and V, read + write
+    extra = {
+        "attention_tflops": att_tflops,
+        "pct_bf16_mfma_peak": 100.0 * att_tflops / PEAK_BF16_TFLOPS,
+        "ms_per_chunk": per_call,
+        "gather_hbm_GBps": gather_bytes / (per_call["gather_hbm"] * 1e-3) / 1e9,
+    }
+
+    if not a.no_pinned and cfg.store == "pinned":
+        # the CPU-offloaded store of the workload definition: same chunks in pinned host memory
+        pk = torch.empty(store_k.shape, dtype=dt, pin_memory=True)
+        pv = torch.empty(store_v.shape, dtype=dt, pin_memory=True)
+        pk.copy_(store_k)
+        pv.copy_(store_v)
+        torch.cuda.synchronize()
+        pstore = wk.Store([pk[c] for c in range(cfg.M)], [pv[c] for c in range(cfg.M)])
+        t_pin = time_call(lambda: wk.wk_gather_window(pstore.desc, ids, n_found, cfg.R, None, None, cfg.n_native,
+                                                      Kw, Vw, N_kv, n_win), 3)
+        link_bytes = 2 * cfg.H * cfg.R * n_out * row_bytes
+        extra["ms_per_chunk"]["gather_pinned_host"] = t_pin
+        extra["gather_pinned_host_GBps"] = link_bytes / (t_pin * 1e-3) / 1e9
+        extra["ms_per_step_pinned_store"] = ms_step - per_call["gather_hbm"] + t_pin
+        # restore the window for the oracle sample below
+        wk.wk_gather_window(store.desc, ids, n_found, cfg.R, Kn, Vn, cfg.n_native, Kw, Vw, N_kv, n_win)
+        torch.cuda.synchronize()
+        del pstore, pk, pv
+
+    out = {
+        "metric": "wk_attention TFLOP/s over the whole hot-path step (compress+score+gather+attend)",
+        "value": flops / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == ws.configs.DT_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): H={cfg.H} d={cfg.d} N_q={cfg.N_q} "
+                               f"N_kv={N_kv} (native {cfg.n_native} + R={cfg.R} x {n_out}), store M={cfg.M}, "
+                               f"rho={cfg.rho}, one layer, one denoising step",
+                   "store": "HBM-resident for the timed step; pinned-host gather reported separately"},
+        "roofline": {"bound": "mfma", "achieved": att_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": att_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "k_attn_bf16", "ms": att_ms, "flop": flops},
+        **extra,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, Q, Kw, Vw, N_kv, evicted, poses_np, cur, n_out, a.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

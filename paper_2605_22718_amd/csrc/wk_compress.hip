@@ -231,7 +231,8 @@ __global__ __launch_bounds__(256) void k_compact(const char *__restrict__ K, con
     const int h = blockIdx.y, b = blockIdx.z;
     if (r >= p.n_out) return;
     const int g = p.G == 1 ? 0 : h;
-    const int src = kept_idx[((size_t)b * p.G + g) * p.n_out + r];
+    int src = kept_idx[((size_t)b * p.G + g) * p.n_out + r];
+    src = src < 0 ? 0 : (src >= p.n_tok ? p.n_tok - 1 : src);  // never read outside the chunk
     constexpr size_t row_bytes = WK_D * (DT == WK_BF16 ? 2 : 4);
     constexpr int vec_per_lane = row_bytes / (kRowLanes * 16);  // 1 (bf16) or 2 (fp32)
     const size_t in_off = (((size_t)b * p.H + h) * p.n_tok + src) * row_bytes;
