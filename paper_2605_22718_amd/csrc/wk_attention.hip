@@ -14,6 +14,7 @@
 // after exp2 and rounding, exactly the B operand of the second product: which key an MFMA
 // "k slot" means is a free choice, as long as the V^T operand uses the same choice.
 #include <cmath>
+#include <type_traits>
 
 #include "wk_internal.h"
 
@@ -23,6 +24,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short i16x8 __attribute__((ext_vector_type(8)));
 
 struct AttnArgs {
     const char *Q;
@@ -183,217 +185,270 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16: v_mfma_f32_32x32x16_bf16, WAVES waves x 32 queries per workgroup, 64-key tiles,
-// K and V^T tiles double-buffered in LDS.
+// bf16: v_mfma_f32_32x32x16_bf16, 8 waves x 32 queries per workgroup, 64-key tiles.
+//
+// K and V tiles go from global memory straight into a 4-deep LDS ring (global_load_lds, no
+// register staging), three tiles ahead of their use.  Both tiles are row-major with their
+// 16-byte chunks permuted inside a row; the permutation is applied on the source side (each
+// lane fetches the chunk that belongs in its linear LDS slot).  K^ operands are plain 16-byte
+// reads; V^T operands are LDS transpose reads (ds_read_b64_tr_b16) of the row-major V tile.
+// While a wave turns S^T of tile j into probabilities and multiplies them into O^T it already
+// computes S^T of tile j+1, so the softmax arithmetic has independent matrix work to hide under.
 // ------------------------------------------------------------------------------------------
-constexpr int kKeys = 64;                    // keys per tile
-constexpr int kKTileBytes = kKeys * 256;     // K tile: [64 keys][16 chunks of 16 B], chunk c of key k at c ^ (k & 15)
-constexpr int kVTileBytes = WK_D * kKeys * 2;  // V^T tile: [128 features][64 key slots]
-constexpr int kStageBytes = kKTileBytes + kVTileBytes;
+constexpr int kKeys = 64;               // keys per tile
+constexpr int kTileBytes = kKeys * 256; // one K or V tile
+constexpr int kStages = 4;
+constexpr int kVRing = kStages * kTileBytes;          // K ring at 0, V ring behind it
+constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 128 KB
 
-// Byte offset of 16-byte chunk c (0..7) of feature row dv in the V^T tile.  Rows are 128 B, two
-// rows per 256-byte bank sweep; XOR-ing the chunk with (dv >> 1) & 7 spreads 16 consecutive rows
-// over all 16 chunk slots.
-__device__ inline int vt_chunk_off(int dv, int c) { return dv * 128 + ((c ^ ((dv >> 1) & 7)) << 4); }
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
-// Slot of key kk (0..63 within the tile) in a V^T row.  Key 32*b + 8*(2*t2 + tt) + 4*g + j sits at
-// slot 32*b + 16*t2 + 8*g + 4*tt + j, so that the 8 accumulator registers 8*t2 .. 8*t2+7 of
-// S^T block b held by lane half g are 8 consecutive slots: one 16-byte read per MFMA operand.
-__device__ inline int vt_slot(int kk) {
-    const int b = kk >> 5, t2 = (kk >> 4) & 1, tt = (kk >> 3) & 1, g = (kk >> 2) & 1, j = kk & 3;
-    return 32 * b + 16 * t2 + 8 * g + 4 * tt + j;
+__device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// max over lanes l and l^32
+__device__ inline float max_across_halves(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int WAVES>
-struct TileRegs {
-    static constexpr int kThreads = WAVES * 64;
-    static constexpr int kKVec = (kKeys * 16) / kThreads;      // 16-byte K chunks per thread
-    static constexpr int kVTask = (kKeys / 4) * 32 / kThreads;  // 4x4 V blocks per thread
-    uint4 k[kKVec];
-    uint2 v[kVTask][4];
-};
+#define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+#define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
-template <int WAVES>
-__device__ inline void load_tile(TileRegs<WAVES> &t, const char *Kh, const char *Vh, int kt, int n_kv, int tid) {
-#pragma unroll
-    for (int i = 0; i < TileRegs<WAVES>::kKVec; ++i) {
-        const int x = tid + i * TileRegs<WAVES>::kThreads;
-        const int key = x >> 4, c = x & 15;
-        t.k[i] = uint4{0, 0, 0, 0};
-        if (kt + key < n_kv) t.k[i] = *reinterpret_cast<const uint4 *>(Kh + (size_t)(kt + key) * 256 + c * 16);
-    }
-#pragma unroll
-    for (int i = 0; i < TileRegs<WAVES>::kVTask; ++i) {
-        const int x = tid + i * TileRegs<WAVES>::kThreads;
-        const int kg = x >> 5, dg = x & 31;  // keys 4*kg .. 4*kg+3, features 4*dg .. 4*dg+3
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int key = kt + 4 * kg + j;
-            t.v[i][j] = uint2{0, 0};  // rows past the window must be zero: their weight is 0, not their value
-            if (key < n_kv) t.v[i][j] = *reinterpret_cast<const uint2 *>(Vh + (size_t)key * 256 + dg * 8);
-        }
-    }
-}
-
-template <int WAVES>
-__device__ inline void store_tile(const TileRegs<WAVES> &t, char *stage, int tid) {
-#pragma unroll
-    for (int i = 0; i < TileRegs<WAVES>::kKVec; ++i) {
-        const int x = tid + i * TileRegs<WAVES>::kThreads;
-        const int key = x >> 4, c = x & 15;
-        *reinterpret_cast<uint4 *>(stage + key * 256 + ((c ^ (key & 15)) << 4)) = t.k[i];
-    }
-    char *vt = stage + kKTileBytes;
-#pragma unroll
-    for (int i = 0; i < TileRegs<WAVES>::kVTask; ++i) {
-        const int x = tid + i * TileRegs<WAVES>::kThreads;
-        const int kg = x >> 5, dg = x & 31;
-        const int slot = vt_slot(4 * kg);  // multiple of 4
-        // 4x4 transpose of 16-bit elements: row j = key, column i = feature
-        const uint32_t r0x = t.v[i][0].x, r1x = t.v[i][1].x, r2x = t.v[i][2].x, r3x = t.v[i][3].x;
-        const uint32_t r0y = t.v[i][0].y, r1y = t.v[i][1].y, r2y = t.v[i][2].y, r3y = t.v[i][3].y;
-        uint2 c0, c1, c2, c3;  // feature 4*dg + 0..3, keys j = 0..3
-        c0.x = __builtin_amdgcn_perm(r1x, r0x, 0x05040100u); c0.y = __builtin_amdgcn_perm(r3x, r2x, 0x05040100u);
-        c1.x = __builtin_amdgcn_perm(r1x, r0x, 0x07060302u); c1.y = __builtin_amdgcn_perm(r3x, r2x, 0x07060302u);
-        c2.x = __builtin_amdgcn_perm(r1y, r0y, 0x05040100u); c2.y = __builtin_amdgcn_perm(r3y, r2y, 0x05040100u);
-        c3.x = __builtin_amdgcn_perm(r1y, r0y, 0x07060302u); c3.y = __builtin_amdgcn_perm(r3y, r2y, 0x07060302u);
-        const int c = slot >> 3, half = (slot >> 2) & 1;
-        const int dv = 4 * dg;
-        *reinterpret_cast<uint2 *>(vt + vt_chunk_off(dv + 0, c) + 8 * half) = c0;
-        *reinterpret_cast<uint2 *>(vt + vt_chunk_off(dv + 1, c) + 8 * half) = c1;
-        *reinterpret_cast<uint2 *>(vt + vt_chunk_off(dv + 2, c) + 8 * half) = c2;
-        *reinterpret_cast<uint2 *>(vt + vt_chunk_off(dv + 3, c) + 8 * half) = c3;
-    }
-}
-
-// Two waves per SIMD in both shapes (one 8-wave workgroup, or two 4-wave workgroups per CU), so
-// that one wave's softmax (VALU) overlaps the other's MFMAs: at most 256 VGPRs per lane.
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
-    extern __shared__ __attribute__((aligned(256))) char smem[];  // 2 stages of (K tile, V^T tile)
+    static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
+    extern __shared__ __attribute__((aligned(256))) char smem[];
     int h, qt;
     if (!work_item(a, h, qt)) return;
     const int n_kv = window_length(a);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
     const int q = qt * (WAVES * 32) + wave * 32 + col;
     const bool q_ok = q < a.N_q;
     const int q_ld = q_ok ? q : a.N_q - 1;
     const char *Qrow = a.Q + ((size_t)h * a.N_q + q_ld) * 256;
-    char *Orow = a.O + ((size_t)h * a.N_q + q_ld) * 256;
 
     if (n_kv == 0) {
         if (q_ok) {
+            char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
             for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
             if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = -INFINITY;
         }
         return;
     }
 
-    // B operand of S^T = K Q^T, step s: features 16*s + 8*g .. +7 of this lane's query
+    // B operand of S^T = K Q^T, step st: features 16*st + 8*g .. +7 of this lane's query
     bf16x8 qb[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) qb[s] = *reinterpret_cast<const bf16x8 *>(Qrow + (2 * s + g) * 16);
+    for (int st = 0; st < 8; ++st) qb[st] = *reinterpret_cast<const bf16x8 *>(Qrow + (2 * st + g) * 16);
+
+    // K tile: row-major, chunk c of key k at slot c ^ (k & 15).  A operand of S^T block b, step st:
+    // key 32*b + col, chunk 2*st + g.   address = k_rd[st] + stage*16384 + b*8192
+    const char *k_rd[8];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) k_rd[st] = smem + col * 256 + (((2 * st + g) ^ (col & 15)) << 4);
+    // V tile: row-major, chunk c of key k at slot c ^ ((k & 3) << 2).  The transpose read hands lane
+    // i of a 16-lane group element (i & 3) of source lane 4*j + (i >> 2), j = 0..3.  Source lane p of
+    // group u points at key 16*ks + 8*tt + 4*g + (p >> 2), features 32*blk + 16*(u&1) + 4*(p&3) .. +3,
+    // so lane i receives feature 32*blk + 16*(u&1) + i of keys 16*ks + 8*tt + 4*g + 0..3: the four
+    // k slots that registers 4*tt .. 4*tt+3 of the P^T operand of step ks stand for.
+    //   address = v_rd[blk] + stage*16384 + ks*4096 + tt*2048
+    const char *v_rd[4];
+    {
+        const int u = lane >> 4, p = lane & 15;
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+            v_rd[blk] = smem + kVRing + (4 * g + (p >> 2)) * 256 +
+                        ((4 * (blk ^ (p >> 2)) + 2 * (u & 1) + ((p & 3) >> 1)) << 4) + 8 * (p & 1);
+    }
+    // tile loads: wave w fills 1 KB blocks 2*w and 2*w+1 of the K tile and of the V tile; lane l of
+    // a block lands in 16-byte slot l = (row r = l >> 4 of the block, slot p = l & 15)
+    unsigned k_src[2], v_src[2];
+    {
+        const int r = lane >> 4, p = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int R = 4 * (2 * wave + i) + r;
+            k_src[i] = R * 256 + ((p ^ (R & 15)) << 4);
+            v_src[i] = R * 256 + ((p ^ (r << 2)) << 4);
+        }
+    }
+    const char *Kh = a.K + (size_t)h * a.kv_row_stride * 256;
+    const char *Vh = a.V + (size_t)h * a.kv_row_stride * 256;
+    const int n_tiles = (n_kv + kKeys - 1) / kKeys;
+    const unsigned last_off = (unsigned)(n_kv - 1) * 256u;
+    char *const dma_dst = smem + wave * 2048;   // + slot*16384 (+ kVRing) + i*1024
+
+    // 4 loads per wave and tile.  Tiles that end past the window clamp their rows to the last one;
+    // those keys are masked (weight exactly 0) before they can contribute.
+    auto issue_tile = [&](int t, int slot) {
+        const unsigned t_off = (unsigned)t * (kKeys * 256u);
+        char *dst = dma_dst + slot * kTileBytes;
+        if ((t + 1) * kKeys <= n_kv) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                __builtin_amdgcn_global_load_lds(WK_GLB(Kh + (t_off + k_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const unsigned ko = min(t_off + k_src[i], last_off + (k_src[i] & 255u));
+                const unsigned vo = min(t_off + v_src[i], last_off + (v_src[i] & 255u));
+                __builtin_amdgcn_global_load_lds(WK_GLB(Kh + ko), WK_LDS(dst + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+            }
+        }
+    };
 
     f32x16 o[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[b][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;   // m_run in scaled (log2) units
+    const float c_log2 = a.scale_log2;
 
-    const char *Kh = a.K + (size_t)h * a.kv_row_stride * 256;
-    const char *Vh = a.V + (size_t)h * a.kv_row_stride * 256;
-    const int n_tiles = (n_kv + kKeys - 1) / kKeys;
-
-    TileRegs<WAVES> regs;
-    load_tile<WAVES>(regs, Kh, Vh, 0, n_kv, tid);
-    store_tile<WAVES>(regs, smem, tid);
-    __syncthreads();
-
-    for (int it = 0; it < n_tiles; ++it) {
-        const int kt = it * kKeys;
-        const char *stage = smem + (it & 1) * kStageBytes;
-        const bool more = it + 1 < n_tiles;
-        if (more) load_tile<WAVES>(regs, Kh, Vh, kt + kKeys, n_kv, tid);
-
-        // S^T blocks: 2 x (32 keys x 32 queries)
-        f32x16 s[2];
+    auto compute_s = [&](int byte_off, f32x16 (&s)[2]) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
-            const int key = 32 * b + col;
+        // the two 32-key blocks are independent accumulation chains: alternate them
 #pragma unroll
-            for (int st = 0; st < 8; ++st) {
-                const bf16x8 ka =
-                    *reinterpret_cast<const bf16x8 *>(stage + key * 256 + (((2 * st + g) ^ (key & 15)) << 4));
+        for (int st = 0; st < 8; ++st)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(k_rd[st] + byte_off + b * 8192);
                 s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[st], s[b], 0, 0, 0);
             }
+    };
+    // scaled row max of a tile's raw logits (both lane halves combined)
+    auto tile_max = [&](const f32x16 (&s)[2]) {
+        float mx[10];
+#pragma unroll
+        for (int i = 0; i < 10; ++i) {
+            const int e = 3 * i;
+            mx[i] = max3(s[e >> 4][e & 15], s[(e + 1) >> 4][(e + 1) & 15], s[(e + 2) >> 4][(e + 2) & 15]);
         }
-        // online softmax in base 2; register r of block b is key kt + 32*b + 8*(r/4) + 4*g + r%4
-        float m_tile = -INFINITY;
-        if (kt + kKeys <= n_kv) {
+        float m = max3(max3(mx[0], mx[1], mx[2]), max3(mx[3], mx[4], mx[5]), max3(mx[6], mx[7], mx[8]));
+        m = max3(m, mx[9], fmaxf(s[1][14], s[1][15]));
+        return max_across_halves(m) * c_log2;
+    };
+    // lazy rescale: the running max only moves when some row's max grew by more than 2^8
+    auto maybe_rescale = [&](float m_tile) {
+        if (__any(m_tile > m_run + 8.0f)) {
+            const float m_new = fmaxf(m_run, m_tile);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    s[b][r] *= a.scale_log2;
-                    m_tile = fmaxf(m_tile, s[b][r]);
+                for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+        }
+    };
+    // p = exp2(s*c - m) rounded to bf16; registers 8*t2 .. 8*t2+7 of block b -> k step 2*b + t2.
+    // The row sum uses the rounded probabilities, the ones the P V product sees.
+    auto probabilities = [&](const f32x16 (&s)[2], bf16x8 (&pb)[4]) {
+        const float neg_m = -m_run;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * t2 + e], c_log2, neg_m));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[b][8 * t2 + e + 1], c_log2, neg_m));
+                    const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
+                    pb[2 * b + t2][e] = pk[0];
+                    pb[2 * b + t2][e + 1] = pk[1];
+                    l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
                 }
-        } else {
+    };
+    auto accumulate_pv = [&](int byte_off, const bf16x8 (&pb)[4]) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const char *p = v_rd[b] + byte_off + ks * 4096;
+                const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p));
+                const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 2048));
+                const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[ks], o[b], 0, 0, 0);
+            }
+    };
+
+    // The ring slot of tile j is (j + sh) & 3 with sh chosen so that the last tile sits in slot 0:
+    // the 4-step unrolled loop below is entered at position sh and always ends on a full group.
+    const int n_steps = n_tiles - 1;
+    const int sh = (4 - (n_steps & 3)) & 3;
+    issue_tile(0, sh);
+    issue_tile(1, (sh + 1) & 3);
+    issue_tile(2, (sh + 2) & 3);
+    __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tiles 0 and 1 of this wave have landed
+    __syncthreads();
+    f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
+    float mt;
+    if (sh & 1) { compute_s(sh * kTileBytes, s_b); mt = tile_max(s_b); }
+    else        { compute_s(sh * kTileBytes, s_a); mt = tile_max(s_a); }
+
+    // one pipeline step: tile j (ring position POS) is consumed, S^T of tile j+1 produced
+    auto step = [&](int j, auto pos_tag, f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) {
+        constexpr int POS = decltype(pos_tag)::value;
+        issue_tile(j + 3, (POS + 3) & 3);
+        maybe_rescale(mt);
+        compute_s(((POS + 1) & 3) * kTileBytes, s_next);
+        bf16x8 pb[4];
+        probabilities(s_cur, pb);
+        accumulate_pv(POS * kTileBytes, pb);
+        mt = tile_max(s_next);
+        __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): everything but tile j+3 has landed
+        __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
+    int j = 0;
+    if (n_steps > 0) {   // partial first group: positions sh .. 3
+        if (sh == 1) { step(j++, P1{}, s_b, s_a); step(j++, P2{}, s_a, s_b); step(j++, P3{}, s_b, s_a); }
+        else if (sh == 2) { step(j++, P2{}, s_a, s_b); step(j++, P3{}, s_b, s_a); }
+        else if (sh == 3) { step(j++, P3{}, s_b, s_a); }
+    }
+    for (; j < n_steps; j += 4) {
+        step(j, P0{}, s_a, s_b);
+        step(j + 1, P1{}, s_b, s_a);
+        step(j + 2, P2{}, s_a, s_b);
+        step(j + 3, P3{}, s_b, s_a);
+    }
+    // last tile (ring position 0, S^T in s_a): the only one that can be partial.  Mask the keys
+    // past the window and redo its max.
+    {
+        const int kt = (n_tiles - 1) * kKeys;
+        if (kt + kKeys > n_kv) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = kt + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
-                    s[b][r] = key < n_kv ? s[b][r] * a.scale_log2 : -INFINITY;
-                    m_tile = fmaxf(m_tile, s[b][r]);
+                    if (key >= n_kv) s_a[b][r] = -INFINITY;
                 }
+            mt = tile_max(s_a);
         }
-        m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
-        const float m_new = fmaxf(m_run, m_tile);  // finite: every tile holds at least one valid key
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        // P^T operands: registers 8*t2 .. 8*t2+7 of block b -> k step 2*b + t2
+        maybe_rescale(mt);
         bf16x8 pb[4];
-        float l_tile = 0.f;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s[b][8 * t2 + e] - m_new);
-                    const float p1 = __builtin_amdgcn_exp2f(s[b][8 * t2 + e + 1] - m_new);
-                    const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
-                    pb[2 * b + t2][e] = pk[0];
-                    pb[2 * b + t2][e + 1] = pk[1];
-                    // the row sum uses the rounded probabilities, the ones the P V product sees
-                    l_tile += (float)pk[0] + (float)pk[1];
-                }
-            }
-        l_run = l_run * alpha + l_tile;
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
-        // O^T += V^T P^T
-        const char *vt = stage + kKTileBytes;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vt + vt_chunk_off(32 * b + col, 2 * ks + g));
-                o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[ks], o[b], 0, 0, 0);
-            }
-
-        if (more) store_tile<WAVES>(regs, smem + ((it + 1) & 1) * kStageBytes, tid);
-        __syncthreads();
+        probabilities(s_a, pb);
+        accumulate_pv(0, pb);
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped look-ahead loads before the LDS is released
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (q_ok) {
+        char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
         const float inv = 1.f / l_tot;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
@@ -417,7 +472,14 @@ wk_status launch_bf16(AttnArgs a, hipStream_t st) {
     a.n_qtiles = (a.N_q + q_per_wg - 1) / q_per_wg;
     const int items = a.H * a.n_qtiles;
     a.per_xcd = (items + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), 2 * kStageBytes, st, a);
+    static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
+    if (!lds_limit_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
+            return WK_ERR_HIP;
+        lds_limit_set = true;
+    }
+    hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
     WK_LAUNCH_CHECK();
     return WK_OK;
 }
@@ -454,9 +516,7 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
         WK_LAUNCH_CHECK();
         return WK_OK;
     }
-    // 256-query workgroups (8 waves, two per SIMD) when that still gives every CU work, else 128.
-    const int items8 = H * ((N_q + 255) / 256);
-    return items8 >= 256 ? launch_bf16<8>(a, st) : launch_bf16<4>(a, st);
+    return launch_bf16<8>(a, st);
 }
 
 extern "C" const char *wk_status_string(wk_status s) {
