@@ -22,6 +22,9 @@ import paper_2605_22718_amd as wk
 import wk_synth as ws
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# HBM bytes per wk_attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs),
+# per workload index; see profiles/hbm_traffic_lingbot_pmc.txt for the commands and the calibration
+MEASURED_ATTENTION_TRAFFIC = {2: (425051 + 63520) * 1024}
 
 
 def parse():
@@ -218,7 +221,8 @@ def main():
                                f"rho={cfg.rho}, one layer, one denoising step",
                    "store": "HBM-resident for the timed step; pinned-host gather reported separately"},
         "roofline": {"bound": "mfma", "achieved": att_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": att_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": att_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_ATTENTION_TRAFFIC.get(cfg.index),
                      "kernel": "k_attn_bf16", "ms": att_ms, "flop": flops},
         **extra,
     }
