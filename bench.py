@@ -103,8 +103,8 @@ def cpu_baseline(cfg, Q, Kw, Vw, N_kv, raw_chunk, poses, cur, n_out, target_s):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the path shards by heads with no exchange; "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (the path shards by heads with no exchange "
+              "between GPUs); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
