@@ -181,6 +181,14 @@ def main():
                                                             Kw, Vw, N_kv, n_win), reps),
         "attention": att_ms,
     }
+    if cfg.dtype == ws.configs.DT_BF16:
+        # Eq. 5 as a similarity GEMM on the matrix cores (same result; reported against the MFMA peak)
+        gdesc = wk.make_compress_desc(cfg.H, cfg.T, cfg.F, cfg.dtype, cfg.rho, ratio_kind=cfg.ratio_kind,
+                                      anchor_mode=cfg.anchor_mode, head_mode=cfg.head_mode,
+                                      score_algo=wk.WK_SCORE_GEMM)
+        gws = torch.empty(wk.wk_compress_workspace_bytes(gdesc), dtype=torch.uint8, device=dev)
+        per_call["compress_gemm_scoring"] = time_call(
+            lambda: wk.wk_compress_chunk(gdesc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k, ev_v, gws), reps)
     row_bytes = cfg.d * Q.element_size()
     gather_bytes = 2 * 2 * cfg.H * N_kv * row_bytes          # K and V, read + write
     extra = {

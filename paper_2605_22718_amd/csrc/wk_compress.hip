@@ -28,19 +28,19 @@ struct CompressDims {
     int n_keep, n_out;
 };
 
-// nsq[(b*G+g)*T + i] = |anchor key i|^2 over the heads of group g
+// out[(b*G+g)*n_rows + i] = |key first_row + i|^2 over the heads of group g; src is [batch][H][rows_per_head][128]
 template <int DT>
-__global__ __launch_bounds__(256) void k_anchor_normsq(const char *__restrict__ A, CompressDims p,
-                                                       double *__restrict__ nsq) {
+__global__ __launch_bounds__(256) void k_rows_normsq(const char *__restrict__ src, CompressDims p, int rows_per_head,
+                                                     int first_row, int n_rows, double *__restrict__ out) {
     const int i = blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
     const int sub = threadIdx.x % kRowLanes;
     const int g = blockIdx.y, b = blockIdx.z;
-    if (i >= p.T) return;
+    if (i >= n_rows) return;
     const size_t row_bytes = WK_D * wk::esize(DT);
     double acc = 0.0;
     for (int hh = 0; hh < p.hg; ++hh) {
         const int h = p.G == 1 ? hh : g;
-        const char *row = A + (((size_t)b * p.H + h) * p.a_rows + i) * row_bytes;
+        const char *row = src + (((size_t)b * p.H + h) * rows_per_head + first_row + i) * row_bytes;
         float v[8];
         load_row8<DT>(row, sub, v);
         float s = 0.f;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void k_anchor_normsq(const char *__restrict__ 
         acc += (double)s;
     }
     acc = wk::row_group_sum(acc);
-    if (sub == 0) nsq[((size_t)b * p.G + g) * p.T + i] = acc;
+    if (sub == 0) out[((size_t)b * p.G + g) * n_rows + i] = acc;
 }
 
 // m[(b*H+h)*128 + c] = (1/T) sum_i A[b][h][i][c] / |anchor key i|   (fp32 result of an fp64 sum)
@@ -117,6 +117,97 @@ __global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__
     if (sub == 0) {
         double s = nacc < 1e-60 ? 0.0 : dacc / sqrt(nacc);
         scores[((size_t)b * p.G + g) * p.n_cand + j] = s + 0.0;  // -0.0 -> +0.0
+    }
+}
+
+// ---- Eq. 5 as a similarity GEMM on the matrix cores (bf16) -------------------------------------
+//
+// scores_j = (1/T) sum_i (k_j . k_i) / (|k_j| |k_i|).  A workgroup owns 64 candidates; for each tile
+// of 64 anchors it accumulates the 64 x 64 block of dot products over all heads of the group
+// (v_mfma_f32_32x32x16_bf16, one 32 x 32 sub-block per wave, raw bf16 keys so every product is exact
+// in fp32), then the epilogue scales column i by 1/|k_i| and adds it into a per-candidate running sum:
+// the (F-1)T x T matrix never leaves registers.  Lane l of a wave holds anchor column l % 32 and
+// candidate rows 8*(r/4) + 4*(l/32) + r%4, so the column scale is a per-lane scalar.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kGemmTile = 64;
+
+__global__ __launch_bounds__(256) void k_score_gemm(const char *__restrict__ K, const char *__restrict__ A,
+                                                    CompressDims p, const double *__restrict__ nsq_a,
+                                                    const double *__restrict__ nsq_c,
+                                                    double *__restrict__ scores) {
+    __shared__ __attribute__((aligned(16))) char At[kGemmTile * 256];   // candidate rows of one head, chunk c at c ^ (row & 15)
+    __shared__ __attribute__((aligned(16))) char Bt[kGemmTile * 256];   // anchor rows of one head
+    __shared__ float part[2][kGemmTile];
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int j0 = blockIdx.x * kGemmTile;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, gh = lane >> 5;
+    const int cs = wave & 1, as = wave >> 1;
+    const double *na = nsq_a + ((size_t)b * p.G + g) * p.T;
+    const double *nc = nsq_c + ((size_t)b * p.G + g) * p.n_cand;
+    float sum[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum[r] = 0.f;
+
+    for (int a0 = 0; a0 < p.T; a0 += kGemmTile) {
+        f32x16 D;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) D[r] = 0.f;
+        for (int hh = 0; hh < p.hg; ++hh) {
+            const int h = p.G == 1 ? hh : g;
+            const char *Kh = K + ((size_t)b * p.H + h) * p.n_tok * 256;
+            const char *Ah = A + ((size_t)b * p.H + h) * p.a_rows * 256;
+            __syncthreads();   // previous head's tiles fully consumed
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int x = tid + i * 256;
+                const int row = x >> 4, c = x & 15;
+                const int cj = min(j0 + row, p.n_cand - 1), ai = min(a0 + row, p.T - 1);   // clamped rows are masked later
+                const uint4 kv = *reinterpret_cast<const uint4 *>(Kh + (size_t)(p.first_cand + cj) * 256 + c * 16);
+                const uint4 av = *reinterpret_cast<const uint4 *>(Ah + (size_t)ai * 256 + c * 16);
+                *reinterpret_cast<uint4 *>(At + row * 256 + ((c ^ (row & 15)) << 4)) = kv;
+                *reinterpret_cast<uint4 *>(Bt + row * 256 + ((c ^ (row & 15)) << 4)) = av;
+            }
+            __syncthreads();
+            const int ra = 32 * cs + col, rb = 32 * as + col;
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(At + ra * 256 + (((2 * st + gh) ^ (ra & 15)) << 4));
+                const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(Bt + rb * 256 + (((2 * st + gh) ^ (rb & 15)) << 4));
+                D = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, kb, D, 0, 0, 0);
+            }
+        }
+        const int i = a0 + 32 * as + col;
+        float rn = 0.f;   // anchors past T (clamped duplicates) and zero-norm anchors contribute nothing
+        if (i < p.T) {
+            const double n2 = na[i];
+            rn = n2 < 1e-60 ? 0.f : (float)(1.0 / sqrt(n2));
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[r] = fmaf(D[r], rn, sum[r]);
+    }
+    // sum over the 32 anchor columns held by the lanes of each half-wave
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float v = sum[r];
+#pragma unroll
+        for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        sum[r] = v;
+    }
+    if (col == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) part[as][32 * cs + 8 * (r >> 2) + 4 * gh + (r & 3)] = sum[r];
+    }
+    __syncthreads();
+    if (tid < kGemmTile) {
+        const int j = j0 + tid;
+        if (j < p.n_cand) {
+            const double tot = (double)part[0][tid] + (double)part[1][tid];
+            const double n2 = nc[j];
+            const double s = n2 < 1e-60 ? 0.0 : tot / (sqrt(n2) * (double)p.T);
+            scores[((size_t)b * p.G + g) * p.n_cand + j] = s + 0.0;
+        }
     }
 }
 
@@ -248,7 +339,7 @@ __global__ __launch_bounds__(256) void k_compact(const char *__restrict__ K, con
 }
 
 struct WsLayout {
-    size_t scores, nsq, mean, kept, total;
+    size_t scores, nsq, nsq_cand, mean, kept, total;
 };
 
 bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
@@ -271,6 +362,9 @@ bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
     size_t off = 0;
     ws.scores = off; off = wk::align_up(off + lists * (size_t)(p.n_cand > 0 ? p.n_cand : 1) * sizeof(double), 256);
     ws.nsq = off;    off = wk::align_up(off + lists * (size_t)p.T * sizeof(double), 256);
+    ws.nsq_cand = off;
+    if (d->score_algo == WK_SCORE_GEMM)
+        off = wk::align_up(off + lists * (size_t)(p.n_cand > 0 ? p.n_cand : 1) * sizeof(double), 256);
     ws.mean = off;   off = wk::align_up(off + (size_t)d->batch * d->H * WK_D * sizeof(float), 256);
     ws.kept = off;   off = wk::align_up(off + lists * (size_t)n_out * sizeof(int32_t), 256);
     ws.total = off;
@@ -286,7 +380,7 @@ wk_status check_desc(const wk_compress_desc *d) {
     if (d->ratio_kind != WK_RATIO_CHUNK && d->ratio_kind != WK_RATIO_NONANCHOR) return WK_ERR_INVALID_ARG;
     if (d->score_algo != WK_SCORE_FACTORED && d->score_algo != WK_SCORE_GEMM) return WK_ERR_INVALID_ARG;
     if (d->d != WK_D) return WK_ERR_UNSUPPORTED;
-    if (d->score_algo == WK_SCORE_GEMM) return WK_ERR_UNSUPPORTED;
+    if (d->score_algo == WK_SCORE_GEMM && d->dtype != WK_BF16) return WK_ERR_UNSUPPORTED;
     if ((int64_t)d->F * d->T > (1 << 24)) return WK_ERR_UNSUPPORTED;
     return WK_OK;
 }
@@ -303,13 +397,28 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
     const char *Kc = reinterpret_cast<const char *>(K);
     if (p.n_cand > 0) {  // scores are always produced: callers may read them from the workspace
         dim3 g1((p.T + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
-        hipLaunchKernelGGL(k_anchor_normsq<DT>, g1, dim3(256), 0, st, A, p, nsq);
+        hipLaunchKernelGGL(k_rows_normsq<DT>, g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
         WK_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_anchor_mean<DT>, dim3(p.H, d->batch), dim3(256), 0, st, A, p, nsq, mean);
-        WK_LAUNCH_CHECK();
-        dim3 g3((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
-        hipLaunchKernelGGL(k_score_factored<DT>, g3, dim3(256), 0, st, Kc, p, mean, scores);
-        WK_LAUNCH_CHECK();
+        if (d->score_algo == WK_SCORE_GEMM) {
+            if constexpr (DT == WK_BF16) {
+                double *nsq_cand = reinterpret_cast<double *>(wsp + ws.nsq_cand);
+                dim3 g2((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
+                hipLaunchKernelGGL(k_rows_normsq<DT>, g2, dim3(256), 0, st, Kc, p, p.n_tok, p.first_cand, p.n_cand,
+                                   nsq_cand);
+                WK_LAUNCH_CHECK();
+                dim3 gg((p.n_cand + kGemmTile - 1) / kGemmTile, p.G, d->batch);
+                hipLaunchKernelGGL(k_score_gemm, gg, dim3(256), 0, st, Kc, A, p, nsq, nsq_cand, scores);
+                WK_LAUNCH_CHECK();
+            } else {
+                return WK_ERR_UNSUPPORTED;
+            }
+        } else {
+            hipLaunchKernelGGL(k_anchor_mean<DT>, dim3(p.H, d->batch), dim3(256), 0, st, A, p, nsq, mean);
+            WK_LAUNCH_CHECK();
+            dim3 g3((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
+            hipLaunchKernelGGL(k_score_factored<DT>, g3, dim3(256), 0, st, Kc, p, mean, scores);
+            WK_LAUNCH_CHECK();
+        }
     }
     hipLaunchKernelGGL(k_select, dim3(d->batch * p.G), dim3(kSelThreads), 0, st, scores, p, kept);
     WK_LAUNCH_CHECK();

@@ -13,12 +13,13 @@ pytestmark = pytest.mark.gpu
 SCORE_TOL = 1e-7   # absolute; the adjacent-score gaps near the cut are a few 1e-6
 
 
-def _gpu_compress(cfg, K, V, K_anchor, batch=1, head_mode=wk.WK_HEADS_SHARED, rho=None, ratio_kind=None):
+def _gpu_compress(cfg, K, V, K_anchor, batch=1, head_mode=wk.WK_HEADS_SHARED, rho=None, ratio_kind=None,
+                  score_algo=wk.WK_SCORE_FACTORED):
     d = dev()
     rho = cfg.rho if rho is None else rho
     ratio_kind = cfg.ratio_kind if ratio_kind is None else ratio_kind
     desc = wk.make_compress_desc(cfg.H, cfg.T, cfg.F, cfg.dtype, rho, batch=batch, head_mode=head_mode,
-                                 anchor_mode=cfg.anchor_mode, ratio_kind=ratio_kind)
+                                 anchor_mode=cfg.anchor_mode, ratio_kind=ratio_kind, score_algo=score_algo)
     n_out, n_keep = wk.wk_keep_count(rho, ratio_kind, cfg.anchor_mode, cfg.F, cfg.T)
     G = cfg.H if head_mode == wk.WK_HEADS_INDEPENDENT else 1
     n_cand = cfg.F * cfg.T - (0 if cfg.anchor_mode == wk.WK_ANCHOR_EXTERNAL else cfg.T)
@@ -108,18 +109,49 @@ def test_exact_ties_go_to_the_lower_index():
     _compare_chunk(cfg, K, V, None, gi[0], gK[0], gV[0], gs[0], wk.WK_HEADS_SHARED, cfg.rho, cfg.ratio_kind)
 
 
+@pytest.mark.parametrize("head_mode", [wk.WK_HEADS_SHARED, wk.WK_HEADS_INDEPENDENT])
+@pytest.mark.parametrize("H,T,F", [(3, 50, 3), (2, 17, 4), (5, 130, 2), (2, 64, 3)])
+def test_gemm_scoring_small_chunks(head_mode, H, T, F):
+    """Eq. 5 as a token-by-anchor similarity GEMM on the matrix cores: same scores, same index sets."""
+    cfg = ws.get_config(1).with_(H=H, T=T, F=F)
+    K, V, _ = ws.make_chunk(cfg, 5)
+    K[:, T + 3] = 0          # a zero candidate and a zero anchor
+    K[:, 1] = 0
+    for rho, kind in [(0.5, wk.WK_RATIO_CHUNK), (0.25, wk.WK_RATIO_NONANCHOR)]:
+        gi, gK, gV, gs, _ = _gpu_compress(cfg, K, V, None, head_mode=head_mode, rho=rho, ratio_kind=kind,
+                                          score_algo=wk.WK_SCORE_GEMM)
+        _compare_chunk(cfg, K, V, None, gi[0], gK[0], gV[0], gs[0], head_mode, rho, kind)
+
+
+def test_gemm_scoring_external_anchor_batch_and_fp32_refusal():
+    cfg = ws.get_config(0).with_(H=2, T=70, dtype=ws.configs.DT_BF16)
+    chunks = [ws.make_chunk(cfg, c) for c in range(2)]
+    K = torch.stack([c[0] for c in chunks])
+    V = torch.stack([c[1] for c in chunks])
+    A = torch.stack([c[2] for c in chunks])
+    gi, gK, gV, gs, n_out = _gpu_compress(cfg, K, V, A, batch=2, score_algo=wk.WK_SCORE_GEMM)
+    for b in range(2):
+        _compare_chunk(cfg, K[b], V[b], A[b], gi[b], gK[b], gV[b], gs[b], wk.WK_HEADS_SHARED, cfg.rho, cfg.ratio_kind)
+    desc = wk.make_compress_desc(2, 70, 1, wk.WK_F32, 0.5, anchor_mode=wk.WK_ANCHOR_EXTERNAL, score_algo=wk.WK_SCORE_GEMM)
+    assert wk.wk_compress_workspace_bytes(desc) == 0      # the matrix-core variant is bf16 only
+
+
+@pytest.mark.parametrize("algo", [wk.WK_SCORE_FACTORED, wk.WK_SCORE_GEMM])
 @pytest.mark.parametrize("ci", [0, 1])
-def test_config_sized_chunk_full_compare(ci):
+def test_config_sized_chunk_full_compare(ci, algo):
+    if ci == 0 and algo == wk.WK_SCORE_GEMM:
+        pytest.skip("config 0 is fp32; the matrix-core scoring variant is bf16 only")
     cfg = ws.get_config(ci)
     K, V, A = ws.make_chunk(cfg, 1)
-    gi, gK, gV, gs, n_out = _gpu_compress(cfg, K, V, A)
+    gi, gK, gV, gs, n_out = _gpu_compress(cfg, K, V, A, score_algo=algo)
     assert n_out == {0: 440, 1: 1320}[ci]
     same = _compare_chunk(cfg, K, V, A, gi[0], gK[0], gV[0], gs[0], wk.WK_HEADS_SHARED, cfg.rho, cfg.ratio_kind)
     print(f"config{ci}: index set identical to the oracle: {same}; max score err {np.abs(gs[0] - oracle.compress_scores(K, A, cfg.T, cfg.F, anchor_mode=cfg.anchor_mode)).max():.2e}")
 
 
+@pytest.mark.parametrize("algo", [wk.WK_SCORE_FACTORED, wk.WK_SCORE_GEMM])
 @pytest.mark.parametrize("head_mode", [wk.WK_HEADS_SHARED, wk.WK_HEADS_INDEPENDENT])
-def test_lingbot_sized_batch_sampled(head_mode):
+def test_lingbot_sized_batch_sampled(head_mode, algo):
     """Config 2/4 shape (H=40, T=1560, F=3), a batch of 2 chunks at P in {0.25, 0.75}: oracle scores on
     sampled candidates, and -- valid at any size -- the kept set is exactly the n_keep lowest of the
     GPU's own scores with ties to the lower index."""
@@ -132,7 +164,7 @@ def test_lingbot_sized_batch_sampled(head_mode):
     sel = np.unique(np.concatenate([[0, 1, 3119, 1559, 1560], rng.integers(0, 3120, 40)])).astype(np.int32)
     for P in (0.25, 0.75):
         gi, gK, gV, gs, n_out = _gpu_compress(cfg, K, V, None, batch=2, head_mode=head_mode, rho=P,
-                                              ratio_kind=wk.WK_RATIO_NONANCHOR)
+                                              ratio_kind=wk.WK_RATIO_NONANCHOR, score_algo=algo)
         n_keep = n_out - cfg.T
         assert n_out == {0.25: 2340, 0.75: 3900}[P]
         for b in range(2):
