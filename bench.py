@@ -129,13 +129,17 @@ def main():
     n_found = torch.empty(1, dtype=torch.int32, device=dev)
     Kw = torch.zeros((cfg.H, N_kv, cfg.d), dtype=dt, device=dev)
     Vw = torch.zeros_like(Kw)
+    Kw[:, :cfg.n_native] = Kn
+    Vw[:, :cfg.n_native] = Vn
     n_win = torch.empty(1, dtype=torch.int32, device=dev)
     O = torch.empty_like(Q)
 
     def step(store_desc, ev_att=None):
         wk.wk_compress_chunk(desc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k, ev_v, wsb)
         wk.wk_score_chunks(poses, cfg.M, cur, wk.WK_NORM_MAX, cfg.R, ids, dist, n_found)
-        wk.wk_gather_window(store_desc, ids, n_found, cfg.R, Kn, Vn, cfg.n_native, Kw, Vw, N_kv, n_win)
+        # the native sliding-window rows already live at the head of the window buffer (K_native = NULL):
+        # only the retrieved chunks move
+        wk.wk_gather_window(store_desc, ids, n_found, cfg.R, None, None, cfg.n_native, Kw, Vw, N_kv, n_win)
         if ev_att:
             ev_att[0].record()
         wk.wk_attention(Q, Kw, Vw, O, None, N_kv=N_kv, n_kv_dev=n_win)
@@ -177,8 +181,10 @@ def main():
                                                            ev_v, wsb), reps),
         "score": time_call(lambda: wk.wk_score_chunks(poses, cfg.M, cur, wk.WK_NORM_MAX, cfg.R, ids, dist, n_found),
                            reps),
-        "gather_hbm": time_call(lambda: wk.wk_gather_window(store.desc, ids, n_found, cfg.R, Kn, Vn, cfg.n_native,
+        "gather_hbm": time_call(lambda: wk.wk_gather_window(store.desc, ids, n_found, cfg.R, None, None, cfg.n_native,
                                                             Kw, Vw, N_kv, n_win), reps),
+        "gather_hbm_with_native_copy": time_call(lambda: wk.wk_gather_window(store.desc, ids, n_found, cfg.R, Kn, Vn,
+                                                                             cfg.n_native, Kw, Vw, N_kv, n_win), reps),
         "attention": att_ms,
     }
     if cfg.dtype == ws.configs.DT_BF16:
@@ -190,7 +196,7 @@ def main():
         per_call["compress_gemm_scoring"] = time_call(
             lambda: wk.wk_compress_chunk(gdesc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k, ev_v, gws), reps)
     row_bytes = cfg.d * Q.element_size()
-    gather_bytes = 2 * 2 * cfg.H * N_kv * row_bytes          # K and V, read + write
+    gather_bytes = 2 * 2 * cfg.H * cfg.R * n_out * row_bytes   # retrieved rows of K and V, read + write
     extra = {
         "attention_tflops": att_tflops,
         "pct_bf16_mfma_peak": 100.0 * att_tflops / PEAK_BF16_TFLOPS,
@@ -213,7 +219,7 @@ def main():
         extra["gather_pinned_host_GBps"] = link_bytes / (t_pin * 1e-3) / 1e9
         extra["ms_per_step_pinned_store"] = ms_step - per_call["gather_hbm"] + t_pin
         # restore the window for the oracle sample below
-        wk.wk_gather_window(store.desc, ids, n_found, cfg.R, Kn, Vn, cfg.n_native, Kw, Vw, N_kv, n_win)
+        wk.wk_gather_window(store.desc, ids, n_found, cfg.R, None, None, cfg.n_native, Kw, Vw, N_kv, n_win)
         torch.cuda.synchronize()
         del pstore, pk, pv
 

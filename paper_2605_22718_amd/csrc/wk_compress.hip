@@ -52,20 +52,26 @@ __global__ __launch_bounds__(256) void k_rows_normsq(const char *__restrict__ sr
     if (sub == 0) out[((size_t)b * p.G + g) * n_rows + i] = acc;
 }
 
-// m[(b*H+h)*128 + c] = (1/T) sum_i A[b][h][i][c] / |anchor key i|   (fp32 result of an fp64 sum)
+// m[(b*H+h)*128 + c] = (1/T) sum_i A[b][h][i][c] / |anchor key i|   (fp32 result of an fp64 sum).
+// The T rows of a head are split over kMeanSplits workgroups (one head alone would keep only H CUs
+// busy); partial sums meet in a fixed order in k_anchor_mean_finish, so the result is deterministic.
+constexpr int kMeanSplits = 16;
+
 template <int DT>
-__global__ __launch_bounds__(256) void k_anchor_mean(const char *__restrict__ A, CompressDims p,
-                                                     const double *__restrict__ nsq,
-                                                     float *__restrict__ m) {
+__global__ __launch_bounds__(256) void k_anchor_mean_partial(const char *__restrict__ A, CompressDims p,
+                                                             const double *__restrict__ nsq,
+                                                             double *__restrict__ partial) {
     __shared__ double red[kRowsPerBlock][WK_D];
-    const int h = blockIdx.x, b = blockIdx.y;
+    const int h = blockIdx.x, sp = blockIdx.y, b = blockIdx.z;
     const int g = p.G == 1 ? 0 : h;
     const int slot = threadIdx.x / kRowLanes, sub = threadIdx.x % kRowLanes;
     const size_t row_bytes = WK_D * wk::esize(DT);
     const char *base = A + ((size_t)b * p.H + h) * p.a_rows * row_bytes;
     const double *nq = nsq + ((size_t)b * p.G + g) * p.T;
+    const int per = (p.T + kMeanSplits - 1) / kMeanSplits;
+    const int i_end = min(p.T, (sp + 1) * per);
     double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int i = slot; i < p.T; i += kRowsPerBlock) {
+    for (int i = sp * per + slot; i < i_end; i += kRowsPerBlock) {
         float v[8];
         load_row8<DT>(base + (size_t)i * row_bytes, sub, v);
         const double n2 = nq[i];
@@ -80,8 +86,17 @@ __global__ __launch_bounds__(256) void k_anchor_mean(const char *__restrict__ A,
         double s = 0.0;
 #pragma unroll
         for (int r = 0; r < kRowsPerBlock; ++r) s += red[r][threadIdx.x];
-        m[((size_t)b * p.H + h) * WK_D + threadIdx.x] = (float)(s / (double)p.T);
+        partial[(((size_t)b * p.H + h) * kMeanSplits + sp) * WK_D + threadIdx.x] = s;
     }
+}
+
+__global__ __launch_bounds__(WK_D) void k_anchor_mean_finish(const double *__restrict__ partial, CompressDims p,
+                                                            float *__restrict__ m) {
+    const size_t bh = (size_t)blockIdx.y * p.H + blockIdx.x;
+    double s = 0.0;
+#pragma unroll
+    for (int sp = 0; sp < kMeanSplits; ++sp) s += partial[(bh * kMeanSplits + sp) * WK_D + threadIdx.x];
+    m[bh * WK_D + threadIdx.x] = (float)(s / (double)p.T);
 }
 
 // scores[(b*G+g)*n_cand + j] = (k_j . m) / |k_j|
@@ -131,61 +146,81 @@ __global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kGemmTile = 64;
+constexpr int kGemmMaxSplits = 8;   // anchor tiles of one candidate tile may be split over this many workgroups
 
+// partial[((b*G+g)*splits + sp)*n_cand + j] = sum over the anchors of split sp of (k_j . k_i) / |k_i|
 __global__ __launch_bounds__(256) void k_score_gemm(const char *__restrict__ K, const char *__restrict__ A,
                                                     CompressDims p, const double *__restrict__ nsq_a,
-                                                    const double *__restrict__ nsq_c,
-                                                    double *__restrict__ scores) {
+                                                    int splits, float *__restrict__ partial) {
     __shared__ __attribute__((aligned(16))) char At[kGemmTile * 256];   // candidate rows of one head, chunk c at c ^ (row & 15)
     __shared__ __attribute__((aligned(16))) char Bt[kGemmTile * 256];   // anchor rows of one head
     __shared__ float part[2][kGemmTile];
-    const int g = blockIdx.y, b = blockIdx.z;
+    const int g = blockIdx.y / splits, sp = blockIdx.y % splits, b = blockIdx.z;
     const int j0 = blockIdx.x * kGemmTile;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, gh = lane >> 5;
     const int cs = wave & 1, as = wave >> 1;
     const double *na = nsq_a + ((size_t)b * p.G + g) * p.T;
-    const double *nc = nsq_c + ((size_t)b * p.G + g) * p.n_cand;
+    const int n_at = (p.T + kGemmTile - 1) / kGemmTile;
+    const int per = (n_at + splits - 1) / splits;
+    const int at_begin = sp * per, at_end = min(n_at, at_begin + per);
     float sum[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum[r] = 0.f;
 
-    for (int a0 = 0; a0 < p.T; a0 += kGemmTile) {
-        f32x16 D;
+    // one iteration = (anchor tile, head); the next iteration's tiles are fetched into registers
+    // while the matrix cores work on the current ones
+    const int n_iter = (at_end - at_begin) * p.hg;
+    uint4 ra[4], rb[4];
+    auto fetch = [&](int it) {
+        const int at = at_begin + it / p.hg, hh = it % p.hg;
+        const int h = p.G == 1 ? hh : g;
+        const char *Kh = K + ((size_t)b * p.H + h) * p.n_tok * 256;
+        const char *Ah = A + ((size_t)b * p.H + h) * p.a_rows * 256;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) D[r] = 0.f;
-        for (int hh = 0; hh < p.hg; ++hh) {
-            const int h = p.G == 1 ? hh : g;
-            const char *Kh = K + ((size_t)b * p.H + h) * p.n_tok * 256;
-            const char *Ah = A + ((size_t)b * p.H + h) * p.a_rows * 256;
-            __syncthreads();   // previous head's tiles fully consumed
+        for (int i = 0; i < 4; ++i) {
+            const int x = tid + i * 256;
+            const int row = x >> 4, c = x & 15;
+            const int cj = min(j0 + row, p.n_cand - 1), ai = min(at * kGemmTile + row, p.T - 1);   // clamped rows are masked later
+            ra[i] = *reinterpret_cast<const uint4 *>(Kh + (size_t)(p.first_cand + cj) * 256 + c * 16);
+            rb[i] = *reinterpret_cast<const uint4 *>(Ah + (size_t)ai * 256 + c * 16);
+        }
+    };
+    if (n_iter > 0) fetch(0);
+    f32x16 D;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int x = tid + i * 256;
-                const int row = x >> 4, c = x & 15;
-                const int cj = min(j0 + row, p.n_cand - 1), ai = min(a0 + row, p.T - 1);   // clamped rows are masked later
-                const uint4 kv = *reinterpret_cast<const uint4 *>(Kh + (size_t)(p.first_cand + cj) * 256 + c * 16);
-                const uint4 av = *reinterpret_cast<const uint4 *>(Ah + (size_t)ai * 256 + c * 16);
-                *reinterpret_cast<uint4 *>(At + row * 256 + ((c ^ (row & 15)) << 4)) = kv;
-                *reinterpret_cast<uint4 *>(Bt + row * 256 + ((c ^ (row & 15)) << 4)) = av;
+    for (int r = 0; r < 16; ++r) D[r] = 0.f;
+    for (int it = 0; it < n_iter; ++it) {
+        __syncthreads();   // previous tiles fully consumed
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int x = tid + i * 256;
+            const int row = x >> 4, c = x & 15;
+            *reinterpret_cast<uint4 *>(At + row * 256 + ((c ^ (row & 15)) << 4)) = ra[i];
+            *reinterpret_cast<uint4 *>(Bt + row * 256 + ((c ^ (row & 15)) << 4)) = rb[i];
+        }
+        __syncthreads();
+        if (it + 1 < n_iter) fetch(it + 1);
+        const int rowa = 32 * cs + col, rowb = 32 * as + col;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(At + rowa * 256 + (((2 * st + gh) ^ (rowa & 15)) << 4));
+            const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(Bt + rowb * 256 + (((2 * st + gh) ^ (rowb & 15)) << 4));
+            D = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, kb, D, 0, 0, 0);
+        }
+        if (it % p.hg == p.hg - 1) {   // all heads of the group accumulated: fold this anchor tile in
+            const int i = (at_begin + it / p.hg) * kGemmTile + 32 * as + col;
+            float rn = 0.f;   // anchors past T (clamped duplicates) and zero-norm anchors contribute nothing
+            if (i < p.T) {
+                const double n2 = na[i];
+                rn = n2 < 1e-60 ? 0.f : (float)(1.0 / sqrt(n2));
             }
-            __syncthreads();
-            const int ra = 32 * cs + col, rb = 32 * as + col;
 #pragma unroll
-            for (int st = 0; st < 8; ++st) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(At + ra * 256 + (((2 * st + gh) ^ (ra & 15)) << 4));
-                const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(Bt + rb * 256 + (((2 * st + gh) ^ (rb & 15)) << 4));
-                D = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, kb, D, 0, 0, 0);
+            for (int r = 0; r < 16; ++r) {
+                sum[r] = fmaf(D[r], rn, sum[r]);
+                D[r] = 0.f;
             }
         }
-        const int i = a0 + 32 * as + col;
-        float rn = 0.f;   // anchors past T (clamped duplicates) and zero-norm anchors contribute nothing
-        if (i < p.T) {
-            const double n2 = na[i];
-            rn = n2 < 1e-60 ? 0.f : (float)(1.0 / sqrt(n2));
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum[r] = fmaf(D[r], rn, sum[r]);
     }
     // sum over the 32 anchor columns held by the lanes of each half-wave
 #pragma unroll
@@ -200,15 +235,22 @@ __global__ __launch_bounds__(256) void k_score_gemm(const char *__restrict__ K, 
         for (int r = 0; r < 16; ++r) part[as][32 * cs + 8 * (r >> 2) + 4 * gh + (r & 3)] = sum[r];
     }
     __syncthreads();
-    if (tid < kGemmTile) {
-        const int j = j0 + tid;
-        if (j < p.n_cand) {
-            const double tot = (double)part[0][tid] + (double)part[1][tid];
-            const double n2 = nc[j];
-            const double s = n2 < 1e-60 ? 0.0 : tot / (sqrt(n2) * (double)p.T);
-            scores[((size_t)b * p.G + g) * p.n_cand + j] = s + 0.0;
-        }
-    }
+    if (tid < kGemmTile && j0 + tid < p.n_cand)
+        partial[(((size_t)b * p.G + g) * splits + sp) * p.n_cand + j0 + tid] = part[0][tid] + part[1][tid];
+}
+
+// scores[(b*G+g)*n_cand + j] = (sum of the splits' partial sums) / (|k_j| T)
+__global__ __launch_bounds__(256) void k_score_gemm_finish(const float *__restrict__ partial, CompressDims p,
+                                                           int splits, const double *__restrict__ nsq_c,
+                                                           double *__restrict__ scores) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const size_t list = blockIdx.y;
+    if (j >= p.n_cand) return;
+    double tot = 0.0;
+    for (int sp = 0; sp < splits; ++sp) tot += (double)partial[(list * splits + sp) * p.n_cand + j];
+    const double n2 = nsq_c[list * p.n_cand + j];
+    const double s = n2 < 1e-60 ? 0.0 : tot / (sqrt(n2) * (double)p.T);
+    scores[list * p.n_cand + j] = s + 0.0;
 }
 
 // ---- selection: n_keep lowest scores of one list, ties to the lower index -------------------
@@ -245,9 +287,13 @@ __device__ inline int block_excl_scan(int v, int *wsum /*[kSelThreads/64]*/, int
 
 // One block per list.  Radix-select (8 passes of 8 bits over order-preserving 64-bit keys) finds
 // the n_keep-th smallest score tau; then tokens with score < tau, plus the first few (by index)
-// with score == tau, are written in ascending index order via block scans.
+// with score == tau, are written in ascending index order via block scans.  Lists of up to
+// kSelLds keys are held in LDS for all passes; longer lists are re-read from global memory.
+constexpr int kSelLds = 6144;   // 48 KB of keys
+
 __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict__ scores,
                                                         CompressDims p, int32_t *__restrict__ kept_idx) {
+    __shared__ uint64_t keys[kSelLds];
     __shared__ unsigned hist[256];
     __shared__ uint64_t s_prefix;
     __shared__ int s_k;
@@ -256,9 +302,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict
     const double *s = scores + (size_t)list * p.n_cand;
     int32_t *out = kept_idx + (size_t)list * p.n_out;
     const int n = p.n_cand, tid = threadIdx.x;
+    const bool in_lds = n <= kSelLds;
 
     for (int i = tid; i < p.first_cand; i += kSelThreads) out[i] = i;  // anchor tokens, kept in full
     if (p.n_keep == 0) return;
+    if (in_lds) {
+        for (int j = tid; j < n; j += kSelThreads) keys[j] = order_key(s[j]);
+        __syncthreads();
+    }
+    auto key_at = [&](int j) { return in_lds ? keys[j] : order_key(s[j]); };
 
     uint64_t prefix = 0;
     int k = p.n_keep;  // rank (1-based) still to locate among keys matching the prefix
@@ -269,19 +321,29 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict
             if (tid < 256) hist[tid] = 0;
             __syncthreads();
             for (int j = tid; j < n; j += kSelThreads) {
-                const uint64_t key = order_key(s[j]);
+                const uint64_t key = key_at(j);
                 if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
             }
             __syncthreads();
-            if (tid == 0) {
-                int cum = 0, bucket = 255;
-                for (int bkt = 0; bkt < 256; ++bkt) {
-                    const int c = (int)hist[bkt];
-                    if (cum + c >= k) { bucket = bkt; break; }
-                    cum += c;
+            // bucket holding rank k: inclusive prefix sums of the 256 counts (4 waves), first one >= k
+            int incl = 0, cnt = 0;
+            if (tid < 256) {
+                cnt = (int)hist[tid];
+                incl = cnt;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int y = __shfl_up(incl, o);
+                    if ((tid & 63) >= o) incl += y;
                 }
-                s_k = k - cum;
-                s_prefix = prefix | ((uint64_t)bucket << shift);
+                if ((tid & 63) == 63) wsum[tid >> 6] = incl;
+            }
+            __syncthreads();
+            if (tid < 256) {
+                for (int w = 0; w < (tid >> 6); ++w) incl += wsum[w];
+                if (incl >= k && incl - cnt < k) {   // exactly one bucket satisfies this
+                    s_k = k - (incl - cnt);
+                    s_prefix = prefix | ((uint64_t)tid << shift);
+                }
             }
             __syncthreads();
             k = s_k;
@@ -295,10 +357,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict
     int eq_base = 0, out_base = 0;
     for (int j0 = 0; j0 < n; j0 += kSelThreads) {
         const int j = j0 + tid;
-        uint64_t key = 0;
         bool less = false, eq = false;
         if (j < n) {
-            key = order_key(s[j]);
+            const uint64_t key = key_at(j);
             less = key < prefix;
             eq = key == prefix;
         }
@@ -339,7 +400,7 @@ __global__ __launch_bounds__(256) void k_compact(const char *__restrict__ K, con
 }
 
 struct WsLayout {
-    size_t scores, nsq, nsq_cand, mean, kept, total;
+    size_t scores, nsq, nsq_cand, gemm_partial, mean, mean_partial, kept, total;
 };
 
 bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
@@ -363,9 +424,16 @@ bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
     ws.scores = off; off = wk::align_up(off + lists * (size_t)(p.n_cand > 0 ? p.n_cand : 1) * sizeof(double), 256);
     ws.nsq = off;    off = wk::align_up(off + lists * (size_t)p.T * sizeof(double), 256);
     ws.nsq_cand = off;
-    if (d->score_algo == WK_SCORE_GEMM)
-        off = wk::align_up(off + lists * (size_t)(p.n_cand > 0 ? p.n_cand : 1) * sizeof(double), 256);
+    ws.gemm_partial = off;
+    if (d->score_algo == WK_SCORE_GEMM) {
+        const size_t nc = (size_t)(p.n_cand > 0 ? p.n_cand : 1);
+        off = wk::align_up(off + lists * nc * sizeof(double), 256);
+        ws.gemm_partial = off;
+        off = wk::align_up(off + lists * kGemmMaxSplits * nc * sizeof(float), 256);
+    }
     ws.mean = off;   off = wk::align_up(off + (size_t)d->batch * d->H * WK_D * sizeof(float), 256);
+    ws.mean_partial = off;
+    off = wk::align_up(off + (size_t)d->batch * d->H * kMeanSplits * WK_D * sizeof(double), 256);
     ws.kept = off;   off = wk::align_up(off + lists * (size_t)n_out * sizeof(int32_t), 256);
     ws.total = off;
     return true;
@@ -406,14 +474,28 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
                 hipLaunchKernelGGL(k_rows_normsq<DT>, g2, dim3(256), 0, st, Kc, p, p.n_tok, p.first_cand, p.n_cand,
                                    nsq_cand);
                 WK_LAUNCH_CHECK();
-                dim3 gg((p.n_cand + kGemmTile - 1) / kGemmTile, p.G, d->batch);
-                hipLaunchKernelGGL(k_score_gemm, gg, dim3(256), 0, st, Kc, A, p, nsq, nsq_cand, scores);
+                // enough workgroups for 256 CUs: split the anchor tiles of a candidate tile if need be
+                const int cand_tiles = (p.n_cand + kGemmTile - 1) / kGemmTile;
+                const int n_at = (p.T + kGemmTile - 1) / kGemmTile;
+                int splits = (512 + cand_tiles * p.G * d->batch - 1) / (cand_tiles * p.G * d->batch);
+                splits = splits < 1 ? 1 : (splits > kGemmMaxSplits ? kGemmMaxSplits : splits);
+                splits = splits > n_at ? n_at : splits;
+                float *partial = reinterpret_cast<float *>(wsp + ws.gemm_partial);
+                hipLaunchKernelGGL(k_score_gemm, dim3(cand_tiles, p.G * splits, d->batch), dim3(256), 0, st, Kc, A, p,
+                                   nsq, splits, partial);
+                WK_LAUNCH_CHECK();
+                hipLaunchKernelGGL(k_score_gemm_finish, dim3((p.n_cand + 255) / 256, d->batch * p.G), dim3(256), 0, st,
+                                   partial, p, splits, nsq_cand, scores);
                 WK_LAUNCH_CHECK();
             } else {
                 return WK_ERR_UNSUPPORTED;
             }
         } else {
-            hipLaunchKernelGGL(k_anchor_mean<DT>, dim3(p.H, d->batch), dim3(256), 0, st, A, p, nsq, mean);
+            double *mean_partial = reinterpret_cast<double *>(wsp + ws.mean_partial);
+            hipLaunchKernelGGL(k_anchor_mean_partial<DT>, dim3(p.H, kMeanSplits, d->batch), dim3(256), 0, st, A, p,
+                               nsq, mean_partial);
+            WK_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_anchor_mean_finish, dim3(p.H, d->batch), dim3(WK_D), 0, st, mean_partial, p, mean);
             WK_LAUNCH_CHECK();
             dim3 g3((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
             hipLaunchKernelGGL(k_score_factored<DT>, g3, dim3(256), 0, st, Kc, p, mean, scores);
