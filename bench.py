@@ -133,6 +133,8 @@ def main():
     Vw[:, :cfg.n_native] = Vn
     n_win = torch.empty(1, dtype=torch.int32, device=dev)
     O = torch.empty_like(Q)
+    att_ws_bytes = wk.wk_attention_workspace_bytes(cfg.H, cfg.N_q, N_kv, cfg.dtype)   # 0 for the LingBot shape
+    att_ws = torch.empty(att_ws_bytes, dtype=torch.uint8, device=dev) if att_ws_bytes else None
 
     def step(store_desc, ev_att=None):
         wk.wk_compress_chunk(desc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k, ev_v, wsb)
@@ -142,7 +144,7 @@ def main():
         wk.wk_gather_window(store_desc, ids, n_found, cfg.R, None, None, cfg.n_native, Kw, Vw, N_kv, n_win)
         if ev_att:
             ev_att[0].record()
-        wk.wk_attention(Q, Kw, Vw, O, None, N_kv=N_kv, n_kv_dev=n_win)
+        wk.wk_attention(Q, Kw, Vw, O, None, N_kv=N_kv, n_kv_dev=n_win, workspace=att_ws)
         if ev_att:
             ev_att[1].record()
 

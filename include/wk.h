@@ -188,10 +188,19 @@ wk_status wk_gather_window(const wk_store_desc *store, const int32_t *ids, const
  *   n_kv_dev   device, int32 or NULL.  If given, min(N_kv, *n_kv_dev) keys are attended (the
  *              length wk_gather_window wrote), read on the device.  A length of 0 gives O = 0
  *              and lse = -inf.
+ *   workspace  device, 256-byte aligned, or NULL.  When H * ceil(N_q / 256) workgroups would leave
+ *              compute units idle (few heads, short query chunk, long window) the key range is split
+ *              over several workgroups whose partial results are merged by a second kernel; that
+ *              needs wk_attention_workspace_bytes(...) bytes.  Without (enough) workspace the call
+ *              runs unsplit: same result up to fp32 rounding order, lower occupancy.
  * Errors: INVALID_ARG, UNSUPPORTED (d != 128), SHAPE (N_kv < 1 or N_kv > kv_row_stride). */
 wk_status wk_attention(const void *Q, const void *K_win, const void *V_win, void *O, float *lse,
                        int32_t H, int32_t N_q, int32_t N_kv, int32_t d, int32_t kv_row_stride,
-                       int32_t dtype, float scale, const int32_t *n_kv_dev, void *hip_stream);
+                       int32_t dtype, float scale, const int32_t *n_kv_dev, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of workspace with which wk_attention splits the key range for this shape (0: it would not). */
+size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype);
 
 /* Device-visible address of a pinned+mapped host allocation (for K_ptr/V_ptr tables and for
  * K_out/V_out of wk_compress_chunk).  Errors: INVALID_ARG, HIP (memory is not pinned). */

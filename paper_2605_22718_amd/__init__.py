@@ -25,7 +25,8 @@ WK_SCORE_MAX_CHUNKS = 4096
 
 EXPORTS = [
     "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
-    "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_host_device_pointer",
+    "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_attention_workspace_bytes",
+    "wk_host_device_pointer",
     "wk_status_string",
 ]
 
@@ -73,7 +74,9 @@ def lib():
         L.wk_gather_window.restype = C.c_int
         L.wk_gather_window.argtypes = [C.POINTER(wk_store_desc), vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, vp]
         L.wk_attention.restype = C.c_int
-        L.wk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp]
+        L.wk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, C.c_size_t, vp]
+        L.wk_attention_workspace_bytes.restype = C.c_size_t
+        L.wk_attention_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.wk_host_device_pointer.restype = C.c_int
         L.wk_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
         L.wk_status_string.restype = C.c_char_p
@@ -203,13 +206,19 @@ def wk_gather_window(store_desc: wk_store_desc, ids, n_ids, R_max, K_native, V_n
     _check(st, "wk_gather_window")
 
 
-def wk_attention(Q, K_win, V_win, O, lse=None, N_kv=None, scale=0.0, n_kv_dev=None):
+def wk_attention_workspace_bytes(H, N_q, N_kv, dtype) -> int:
+    return lib().wk_attention_workspace_bytes(H, N_q, N_kv, dtype)
+
+
+def wk_attention(Q, K_win, V_win, O, lse=None, N_kv=None, scale=0.0, n_kv_dev=None, workspace=None):
     """wk_attention.  Q [H][N_q][d]; K_win/V_win [H][stride][d]; O like Q (written in place)."""
     H, N_q, d = Q.shape
     stride = K_win.shape[1]
     N_kv = stride if N_kv is None else N_kv
     st = lib().wk_attention(_dev(Q, "Q"), _dev(K_win, "K_win", Q.dtype), _dev(V_win, "V_win", Q.dtype),
                             _dev(O, "O", Q.dtype), _dev(lse, "lse", torch.float32), H, N_q, N_kv, d, stride,
-                            dtype_code(Q), scale, _dev(n_kv_dev, "n_kv_dev", torch.int32), _stream())
+                            dtype_code(Q), scale, _dev(n_kv_dev, "n_kv_dev", torch.int32),
+                            _dev(workspace, "workspace"),
+                            0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(st, "wk_attention")
     return O

@@ -37,6 +37,9 @@ struct AttnArgs {
     const int32_t *n_kv_dev;
     int n_qtiles;
     int per_xcd;       // work items per XCD in the launch order
+    int splits;        // key-range splits per (head, query tile); 1 = none
+    float *part_o;     // splits > 1: [splits][H][N_q][128] unnormalised fp32 partial outputs
+    float *part_ml;    //             [splits][H][N_q][2] running max (log2 units) and row sum
 };
 
 constexpr int kXcds = 8;
@@ -45,12 +48,16 @@ constexpr int kXcds = 8;
 // head-major (all query tiles of head 0, then head 1, ...); giving XCD x the contiguous range
 // [x*per_xcd, (x+1)*per_xcd) keeps the query tiles that stream the same head's K/V on one XCD,
 // so that head's window is fetched from HBM once into that XCD's L2 instead of once per tile.
-__device__ inline bool work_item(const AttnArgs &a, int &h, int &qt) {
+// With a split key range the items of one head are ordered split-major, so the query tiles that
+// stream the same slice of K/V stay neighbours.
+__device__ inline bool work_item(const AttnArgs &a, int &h, int &qt, int &sp) {
     const int lin = blockIdx.x;
     const int w = (lin % kXcds) * a.per_xcd + lin / kXcds;
-    if (lin / kXcds >= a.per_xcd || w >= a.H * a.n_qtiles) return false;
-    h = w / a.n_qtiles;
-    qt = w % a.n_qtiles;
+    if (lin / kXcds >= a.per_xcd || w >= a.H * a.n_qtiles * a.splits) return false;
+    h = w / (a.n_qtiles * a.splits);
+    const int rem = w % (a.n_qtiles * a.splits);
+    sp = rem / a.n_qtiles;
+    qt = rem % a.n_qtiles;
     return true;
 }
 
@@ -74,8 +81,8 @@ constexpr int kF32VPitch = WK_D + 8;  // rows 4 apart land 32 banks apart
 __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
     __shared__ float Ks[kF32Keys * kF32KPitch];
     __shared__ float Vs[kF32Keys * kF32VPitch];
-    int h, qt;
-    if (!work_item(a, h, qt)) return;
+    int h, qt, sp;
+    if (!work_item(a, h, qt, sp)) return;
     const int n_kv = window_length(a);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
@@ -219,8 +226,8 @@ template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
     extern __shared__ __attribute__((aligned(256))) char smem[];
-    int h, qt;
-    if (!work_item(a, h, qt)) return;
+    int h, qt, sp;
+    if (!work_item(a, h, qt, sp)) return;
     const int n_kv = window_length(a);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -230,11 +237,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     const int q_ld = q_ok ? q : a.N_q - 1;
     const char *Qrow = a.Q + ((size_t)h * a.N_q + q_ld) * 256;
 
-    if (n_kv == 0) {
+    // this workgroup's tiles [t0, t1) of the window
+    const int n_tiles = (n_kv + kKeys - 1) / kKeys;
+    const int tiles_per_split = (n_tiles + a.splits - 1) / a.splits;
+    const int t0 = sp * tiles_per_split;
+    const int t1 = min(n_tiles, t0 + tiles_per_split);
+    if (t0 >= t1) {   // empty window, or a split past its end: contributes nothing
         if (q_ok) {
-            char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
-            for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
-            if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = -INFINITY;
+            if (a.splits == 1) {
+                char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+                for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
+                if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = -INFINITY;
+            } else {
+                const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
+                for (int c = g * 16; c < g * 16 + 16; ++c) reinterpret_cast<float4 *>(a.part_o + row * WK_D)[c] = float4{0, 0, 0, 0};
+                if (g == 0) { a.part_ml[row * 2] = -INFINITY; a.part_ml[row * 2 + 1] = 0.f; }
+            }
         }
         return;
     }
@@ -277,7 +295,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     }
     const char *Kh = a.K + (size_t)h * a.kv_row_stride * 256;
     const char *Vh = a.V + (size_t)h * a.kv_row_stride * 256;
-    const int n_tiles = (n_kv + kKeys - 1) / kKeys;
     const unsigned last_off = (unsigned)(n_kv - 1) * 256u;
     char *const dma_dst = smem + wave * 2048;   // + slot*16384 (+ kVRing) + i*1024
 
@@ -384,11 +401,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
 
     // The ring slot of tile j is (j + sh) & 3 with sh chosen so that the last tile sits in slot 0:
     // the 4-step unrolled loop below is entered at position sh and always ends on a full group.
-    const int n_steps = n_tiles - 1;
+    const int n_steps = t1 - t0 - 1;
     const int sh = (4 - (n_steps & 3)) & 3;
-    issue_tile(0, sh);
-    issue_tile(1, (sh + 1) & 3);
-    issue_tile(2, (sh + 2) & 3);
+    issue_tile(t0, sh);
+    issue_tile(t0 + 1, (sh + 1) & 3);
+    issue_tile(t0 + 2, (sh + 2) & 3);
     __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tiles 0 and 1 of this wave have landed
     __syncthreads();
     f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
@@ -399,7 +416,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     // one pipeline step: tile j (ring position POS) is consumed, S^T of tile j+1 produced
     auto step = [&](int j, auto pos_tag, f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) {
         constexpr int POS = decltype(pos_tag)::value;
-        issue_tile(j + 3, (POS + 3) & 3);
+        issue_tile(t0 + j + 3, (POS + 3) & 3);
         maybe_rescale(mt);
         compute_s(((POS + 1) & 3) * kTileBytes, s_next);
         bf16x8 pb[4];
@@ -428,7 +445,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     // last tile (ring position 0, S^T in s_a): the only one that can be partial.  Mask the keys
     // past the window and redo its max.
     {
-        const int kt = (n_tiles - 1) * kKeys;
+        const int kt = (t1 - 1) * kKeys;
         if (kt + kKeys > n_kv) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
@@ -447,7 +464,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped look-ahead loads before the LDS is released
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (q_ok) {
+    if (q_ok && a.splits == 1) {
         char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
         const float inv = 1.f / l_tot;
 #pragma unroll
@@ -463,14 +480,80 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                 *reinterpret_cast<uint2 *>(Orow + dv * 2) = w;
             }
         if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+    } else if (q_ok) {   // partial result of this key range, merged by k_attn_merge
+        const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
+        float *Po = a.part_o + row * WK_D;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                *reinterpret_cast<float4 *>(Po + 32 * b + 8 * t + 4 * g) =
+                    float4{o[b][4 * t], o[b][4 * t + 1], o[b][4 * t + 2], o[b][4 * t + 3]};
+        if (g == 0) { a.part_ml[row * 2] = m_run; a.part_ml[row * 2 + 1] = l_tot; }
     }
 }
 
+// Merge of the key-range splits: O = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, m = max_s m_s.
+// 16 lanes per query row, 8 features each; fixed summation order.
+__global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
+    const size_t row = (size_t)blockIdx.x * 16 + threadIdx.x / 16;   // h * N_q + q
+    const int sub = threadIdx.x % 16;
+    const size_t rows = (size_t)a.H * a.N_q;
+    if (row >= rows) return;
+    float m = -INFINITY;
+    for (int s = 0; s < a.splits; ++s) m = fmaxf(m, a.part_ml[((size_t)s * rows + row) * 2]);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float l = 0.f;
+    for (int s = 0; s < a.splits; ++s) {
+        const float ms = a.part_ml[((size_t)s * rows + row) * 2];
+        if (ms == -INFINITY) continue;   // empty split
+        const float w = __builtin_amdgcn_exp2f(ms - m);
+        l = fmaf(w, a.part_ml[((size_t)s * rows + row) * 2 + 1], l);
+        const float4 *po = reinterpret_cast<const float4 *>(a.part_o + ((size_t)s * rows + row) * WK_D) + 2 * sub;
+        const float4 x = po[0], y = po[1];
+        acc[0] = fmaf(w, x.x, acc[0]); acc[1] = fmaf(w, x.y, acc[1]); acc[2] = fmaf(w, x.z, acc[2]); acc[3] = fmaf(w, x.w, acc[3]);
+        acc[4] = fmaf(w, y.x, acc[4]); acc[5] = fmaf(w, y.y, acc[5]); acc[6] = fmaf(w, y.z, acc[6]); acc[7] = fmaf(w, y.w, acc[7]);
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    uint4 out;
+    uint32_t *ow = reinterpret_cast<uint32_t *>(&out);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        ow[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{acc[2 * e] * inv, acc[2 * e + 1] * inv}, bf16x2));
+    reinterpret_cast<uint4 *>(a.O + row * 256)[sub] = out;
+    if (a.lse && sub == 0) a.lse[row] = l > 0.f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+}
+
+// Key-range splits for grids that would leave compute units idle: the count (at most 8, at least
+// 8 tiles per split) that fills the 256 CUs best over whole rounds of workgroups; ties go to fewer.
+int choose_splits(int items, int n_tiles) {
+    int best = 1;
+    double best_util = 0.0;
+    for (int s = 1; s <= 8 && (s == 1 || n_tiles / s >= 8); ++s) {
+        const int wgs = items * s;
+        const double util = (double)wgs / (double)(((wgs + 255) / 256) * 256);
+        if (util > best_util + 0.02) { best_util = util; best = s; }
+    }
+    return best;
+}
+
+size_t split_workspace_bytes(int H, int N_q, int splits) {
+    const size_t rows = (size_t)splits * H * N_q;
+    return wk::align_up(rows * WK_D * sizeof(float), 256) + wk::align_up(rows * 2 * sizeof(float), 256);
+}
+
 template <int WAVES>
-wk_status launch_bf16(AttnArgs a, hipStream_t st) {
+wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipStream_t st) {
     const int q_per_wg = WAVES * 32;
     a.n_qtiles = (a.N_q + q_per_wg - 1) / q_per_wg;
-    const int items = a.H * a.n_qtiles;
+    a.splits = choose_splits(a.H * a.n_qtiles, (a.N_kv + kKeys - 1) / kKeys);
+    if (a.splits > 1 && (!workspace || workspace_bytes < split_workspace_bytes(a.H, a.N_q, a.splits) ||
+                         reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
+        a.splits = 1;   // no room for partial results: one workgroup walks the whole window
+    a.part_o = reinterpret_cast<float *>(workspace);
+    a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                          wk::align_up((size_t)a.splits * a.H * a.N_q * WK_D * sizeof(float), 256));
+    const int items = a.H * a.n_qtiles * a.splits;
     a.per_xcd = (items + kXcds - 1) / kXcds;
     static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
     if (!lds_limit_set) {
@@ -481,6 +564,11 @@ wk_status launch_bf16(AttnArgs a, hipStream_t st) {
     }
     hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
     WK_LAUNCH_CHECK();
+    if (a.splits > 1) {
+        const size_t rows = (size_t)a.H * a.N_q;
+        hipLaunchKernelGGL(k_attn_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
+        WK_LAUNCH_CHECK();
+    }
     return WK_OK;
 }
 
@@ -488,7 +576,8 @@ wk_status launch_bf16(AttnArgs a, hipStream_t st) {
 
 extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *V_win, void *O, float *lse,
                                   int32_t H, int32_t N_q, int32_t N_kv, int32_t d, int32_t kv_row_stride,
-                                  int32_t dtype, float scale, const int32_t *n_kv_dev, void *hip_stream) {
+                                  int32_t dtype, float scale, const int32_t *n_kv_dev, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream) {
     if (!Q || !K_win || !V_win || !O) return WK_ERR_INVALID_ARG;
     if (H < 1 || N_q < 0 || d < 1) return WK_ERR_INVALID_ARG;
     if (dtype != WK_F32 && dtype != WK_BF16) return WK_ERR_INVALID_ARG;
@@ -506,6 +595,9 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     const float sc = scale == 0.f ? 1.f / std::sqrt((float)d) : scale;
     a.scale_log2 = sc * 1.4426950408889634f;
     a.n_kv_dev = n_kv_dev;
+    a.splits = 1;
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     if (dtype == WK_F32) {
         const int q_per_wg = kF32Waves * 32;
@@ -516,7 +608,13 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
         WK_LAUNCH_CHECK();
         return WK_OK;
     }
-    return launch_bf16<8>(a, st);
+    return launch_bf16<8>(a, workspace, workspace_bytes, st);
+}
+
+extern "C" size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype) {
+    if (H < 1 || N_q < 1 || N_kv < 1 || dtype != WK_BF16) return 0;
+    const int splits = choose_splits(H * ((N_q + 255) / 256), (N_kv + kKeys - 1) / kKeys);
+    return splits > 1 ? split_workspace_bytes(H, N_q, splits) : 0;
 }
 
 extern "C" const char *wk_status_string(wk_status s) {

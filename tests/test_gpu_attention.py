@@ -23,12 +23,18 @@ def _rand(H, Nq, Nkv, dtype, seed, stride=None):
     return Q, K, V
 
 
-def _run(Q, K, V, N_kv=None, scale=0.0, n_kv_dev=None, want_lse=True):
+def _workspace(H, N_q, N_kv, dtype):
+    n = wk.wk_attention_workspace_bytes(H, N_q, N_kv, wk.WK_BF16 if dtype == torch.bfloat16 else wk.WK_F32)
+    return torch.empty(n, dtype=torch.uint8, device=dev()) if n else None
+
+
+def _run(Q, K, V, N_kv=None, scale=0.0, n_kv_dev=None, want_lse=True, split=True):
     d = dev()
     O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=d)
     lse = torch.full(Q.shape[:2], float("nan"), dtype=torch.float32, device=d) if want_lse else None
     nk = None if n_kv_dev is None else torch.tensor([n_kv_dev], dtype=torch.int32, device=d)
-    wk.wk_attention(Q.to(d), K.to(d), V.to(d), O, lse, N_kv=N_kv, scale=scale, n_kv_dev=nk)
+    wsb = _workspace(Q.shape[0], Q.shape[1], K.shape[1] if N_kv is None else N_kv, Q.dtype) if split else None
+    wk.wk_attention(Q.to(d), K.to(d), V.to(d), O, lse, N_kv=N_kv, scale=scale, n_kv_dev=nk, workspace=wsb)
     torch.cuda.synchronize()
     return O, lse
 
@@ -97,6 +103,23 @@ def test_normalisation_and_special_cases(dtype):
     _check(Qb, Ks, Vs, O, lse, f32_tol=2e-4)
 
 
+@pytest.mark.parametrize("H,Nq,Nkv,n_dev", [(1, 64, 4000, None), (2, 300, 2048, None), (1, 33, 4096, 100),
+                                            (1, 40, 4096, 0), (3, 257, 1111, 1000)])
+def test_split_key_range_matches_oracle_and_unsplit(H, Nq, Nkv, n_dev):
+    """Few workgroups and a long window: the key range is split over workgroups and merged."""
+    Q, K, V = _rand(H, Nq, Nkv, torch.bfloat16, seed=Nkv + Nq)
+    assert wk.wk_attention_workspace_bytes(H, Nq, Nkv, wk.WK_BF16) > 0
+    O, lse = _run(Q, K, V, n_kv_dev=n_dev)
+    O1, lse1 = _run(Q, K, V, n_kv_dev=n_dev, split=False)
+    if n_dev == 0:
+        assert (O == 0).all() and torch.isinf(lse).all() and (O1 == 0).all()
+        return
+    n_eff = Nkv if n_dev is None else n_dev
+    _check(Q, K, V, O, lse, N_kv=n_eff)
+    _check(Q, K, V, O1, lse1, N_kv=n_eff)
+    assert (O.float() - O1.float()).abs().max().item() <= 4e-3     # same math, different fp32 summation order
+
+
 def test_config0_tiny_fp32_full():
     cfg = ws.get_config(0)
     Q = ws.make_queries(cfg)
@@ -119,7 +142,9 @@ def test_full_size_configs_sampled_rows(ci, n_random):
     K, V = ws.make_native(cfg, d, n_rows=N_kv)
     O = torch.empty_like(Q)
     lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=d)
-    wk.wk_attention(Q, K, V, O, lse)
+    wsb = _workspace(cfg.H, cfg.N_q, N_kv, Q.dtype)      # configs 1 and 3 split the key range, config 2 does not
+    assert (wsb is None) == (ci == 2)
+    wk.wk_attention(Q, K, V, O, lse, workspace=wsb)
     torch.cuda.synchronize()
     rows = sample_rows(cfg.N_q, 256, n_random, seed=ci)
     if ci == 3:
@@ -129,5 +154,5 @@ def test_full_size_configs_sampled_rows(ci, n_random):
     # properties that hold at any size: finite everywhere, V = 1 gives exactly-normalised rows
     assert torch.isfinite(O.float()).all()
     if ci != 3:
-        wk.wk_attention(Q, K, torch.ones_like(V), O, None)
+        wk.wk_attention(Q, K, torch.ones_like(V), O, None, workspace=wsb)
         assert (O.float() - 1).abs().max().item() <= 1e-2

@@ -103,13 +103,18 @@ def test_argument_validation_of_the_other_calls():
     def attn(**kw):
         a = dict(args, **kw)
         return L.wk_attention(one, one, one, one, None, a["H"], a["N_q"], a["N_kv"], a["d"], a["stride"],
-                              a["dtype"], 0.0, None, None)
+                              a["dtype"], 0.0, None, None, 0, None)
     assert attn(d=64) == wk.WK_ERR_UNSUPPORTED
     assert attn(N_kv=0) == wk.WK_ERR_SHAPE
     assert attn(N_kv=9) == wk.WK_ERR_SHAPE
     assert attn(dtype=5) == wk.WK_ERR_INVALID_ARG
     assert attn(H=0) == wk.WK_ERR_INVALID_ARG
-    assert L.wk_attention(None, one, one, one, None, 2, 8, 8, 128, 8, 1, 0.0, None, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_attention(None, one, one, one, None, 2, 8, 8, 128, 8, 1, 0.0, None, None, 0, None) == wk.WK_ERR_INVALID_ARG
+    # key-range splits are only proposed when the plain grid would leave compute units idle
+    assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
+    assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4
+    assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_F32) == 0
+    assert wk.wk_attention_workspace_bytes(1, 64, 128, wk.WK_BF16) == 0      # too short to split
     # gather
     sd = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 128, wk.WK_BF16)
     assert L.wk_gather_window(C.byref(sd), one, None, 2, one, one, 5, one, one, 24, None, None) == wk.WK_ERR_SHAPE
