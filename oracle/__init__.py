@@ -179,3 +179,21 @@ def attention(Q, K, V, N_kv=None, scale=None, rows=None, want_lse=False):
                              C.c_int64(stride), C.c_double(scale), _p(rows), C.c_int64(n_rows), _p(O), _p(lse))
     assert rc == 0, rc
     return (O, lse) if want_lse else O
+
+
+def score_chunks_query(Q, K_chunks, R, scale=None):
+    """Query-based retrieval: ids [min(R,M)], mass_sel, mass_all [M] (attention mass per stored chunk)."""
+    _chk(Q)
+    H, N_q, d = Q.shape
+    M = len(K_chunks)
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    kp = (C.c_void_p * max(M, 1))(*[_chk(c).data_ptr() for c in K_chunks])
+    n_tok = np.array([c.shape[1] for c in K_chunks] or [0], np.int32)
+    ids = np.zeros(max(R, 1), np.int32)
+    m_sel = np.zeros(max(R, 1), np.float64)
+    m_all = np.zeros(max(M, 1), np.float64)
+    n = C.c_int32()
+    rc = lib().wko_score_chunks_query(_p(Q), kp, _p(n_tok), M, _code(Q), H, C.c_int64(N_q), d, C.c_double(scale), R,
+                                      _p(ids), _p(m_sel), _p(m_all), C.byref(n))
+    assert rc == 0, rc
+    return ids[: n.value].copy(), m_sel[: n.value].copy(), m_all[:M].copy()

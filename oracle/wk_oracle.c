@@ -16,6 +16,11 @@
  *   wko_score_chunks
  *        camera/action retrieval distance (Sec. 5.1, implementation details)
  *        and Top-k of Eq. 4 (Sec. 4.2).
+ *   wko_score_chunks_query
+ *        query-based retrieval (Sec. 4.2, App. C): chunks ranked by the attention mass
+ *        of the current queries.  The paper does not define the score further; the
+ *        reading here (joint softmax over all candidates, mean over heads and
+ *        queries) is pinned by invariants only: parity unpinned.
  *   wko_accumulate_actions
  *        discrete actions -> pseudo-pose (Sec. 5.1).  The step constants are
  *        this build's own choice (the paper gives none): parity unpinned
@@ -324,6 +329,83 @@ int wko_score_chunks(const float *poses, int M, const float *cur, int norm_mode,
     }
     free(dt); free(dr); free(p);
     return 0;
+}
+
+/* Query-based retrieval (Sec. 4.2: the relevance function may be a "query-based importance
+ * score"; App. C: stored chunks ranked "by their attention scores with respect to the current
+ * denoising query").  Reading: the relevance of chunk c is the attention mass its keys receive from
+ * the current queries in one softmax over the keys of all M candidate chunks, averaged over heads
+ * and query rows; the min(R, M) chunks of largest mass are returned, ties to the lower chunk id.
+ * Parity with the authors' exact score (which layers, heads or queries they average) is unpinned.
+ * Q [H][N_q][d]; chunk c has keys K_ptrs[c] = [H][n_tok[c]][d].  mass_all [M] (may be NULL). */
+int wko_score_chunks_query(const void *Q, const void *const *K_ptrs, const int32_t *n_tok, int M, int dtype,
+                           int H, int64_t N_q, int d, double scale, int R, int32_t *ids_out, double *mass_sel,
+                           double *mass_all, int32_t *n_found)
+{
+    if (M < 0 || R < 0 || !Q || !n_found || H < 1 || N_q < 1) return -1;
+    int n = R < M ? R : M;
+    *n_found = n;
+    if (M == 0) return 0;
+    double *mass = (double *)calloc((size_t)M, sizeof(double));
+    wko_pair *p = (wko_pair *)malloc(sizeof(wko_pair) * M);
+    if (!mass || !p) { free(mass); free(p); return -2; }
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *local = (double *)calloc((size_t)M, sizeof(double));
+        double *q = (double *)malloc(sizeof(double) * (size_t)d);
+        int64_t max_tok = 0;
+        for (int c = 0; c < M; ++c) if (n_tok[c] > max_tok) max_tok = n_tok[c];
+        double **z = (double **)malloc(sizeof(double *) * (size_t)M);   /* logits per chunk */
+        int ok = local && q && z;
+        if (ok) for (int c = 0; c < M; ++c) { z[c] = (double *)malloc(sizeof(double) * (size_t)(n_tok[c] > 0 ? n_tok[c] : 1)); ok = ok && z[c]; }
+        if (!ok) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 4)
+            for (int h = 0; h < H; ++h)
+                for (int64_t r = 0; r < N_q; ++r) {
+                    for (int e = 0; e < d; ++e) q[e] = load_elem(Q, dtype, ((size_t)h * N_q + r) * d + e);
+                    double zmax = -INFINITY;
+                    for (int c = 0; c < M; ++c)
+                        for (int64_t k = 0; k < n_tok[c]; ++k) {
+                            size_t base = ((size_t)h * n_tok[c] + k) * d;
+                            double dot = 0.0;
+                            for (int e = 0; e < d; ++e) dot += q[e] * load_elem(K_ptrs[c], dtype, base + e);
+                            z[c][k] = dot * scale;
+                            if (z[c][k] > zmax) zmax = z[c][k];
+                        }
+                    double denom = 0.0;
+                    for (int c = 0; c < M; ++c)
+                        for (int64_t k = 0; k < n_tok[c]; ++k) { z[c][k] = exp(z[c][k] - zmax); denom += z[c][k]; }
+                    for (int c = 0; c < M; ++c) {
+                        double sum = 0.0;
+                        for (int64_t k = 0; k < n_tok[c]; ++k) sum += z[c][k];
+                        local[c] += sum / denom;
+                    }
+                }
+#pragma omp critical
+            for (int c = 0; c < M; ++c) mass[c] += local[c];
+        }
+        if (z) for (int c = 0; c < M; ++c) free(z[c]);
+        free(z); free(local); free(q);
+    }
+    if (!fail) {
+        for (int c = 0; c < M; ++c) {
+            mass[c] /= (double)H * (double)N_q;
+            if (mass_all) mass_all[c] = mass[c];
+            p[c].s = -mass[c];   /* largest mass first, ties to the lower id */
+            p[c].idx = c;
+        }
+        qsort(p, (size_t)M, sizeof(wko_pair), cmp_pair);
+        for (int i = 0; i < n; ++i) {
+            ids_out[i] = p[i].idx;
+            if (mass_sel) mass_sel[i] = mass[p[i].idx];
+        }
+    }
+    free(mass); free(p);
+    return fail ? -2 : 0;
 }
 
 /* Accumulate discrete actions into pseudo-poses (Sec. 5.1).  Labels:

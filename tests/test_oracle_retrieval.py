@@ -147,3 +147,59 @@ def test_accumulate_actions_closed_cases():
     assert poses.shape == (1000, 5) and np.isfinite(poses).all()
     ids, _, _ = oracle.score_chunks(poses, poses[500], 4)
     assert ids[0] == 500 or np.allclose(poses[ids[0]], poses[500])
+
+
+# ---- query-based retrieval (Sec. 4.2, App. C) ---------------------------------------------------
+
+def _query_setup(seed=0, H=2, Nq=9, d=8, lens=(5, 7, 3, 6)):
+    import torch
+    g = torch.Generator().manual_seed(seed)
+    Q = torch.randn(H, Nq, d, generator=g)
+    Ks = [torch.randn(H, n, d, generator=g) for n in lens]
+    return Q, Ks
+
+
+def test_query_retrieval_mass_against_library_softmax():
+    import torch
+    Q, Ks = _query_setup(1)
+    ids, m_sel, m_all = oracle.score_chunks_query(Q, Ks, 2)
+    K_all = torch.cat(Ks, 1).double()
+    P = torch.softmax(torch.einsum("hqd,hkd->hqk", Q.double(), K_all) / math.sqrt(Q.shape[-1]), -1)
+    bounds = np.cumsum([0] + [k.shape[1] for k in Ks])
+    expect = np.array([P[:, :, bounds[c]:bounds[c + 1]].sum(-1).mean().item() for c in range(len(Ks))])
+    np.testing.assert_allclose(m_all, expect, atol=1e-14)
+    assert abs(m_all.sum() - 1.0) < 1e-13                    # masses of all candidates sum to one
+    order = np.lexsort((np.arange(len(Ks)), -m_all))[:2]
+    np.testing.assert_array_equal(ids, order)
+    np.testing.assert_allclose(m_sel, m_all[order], atol=0)
+    # the mass of a chunk is what attention returns for V = indicator of that chunk (window = all candidates)
+    ind = torch.zeros(K_all.shape[0], K_all.shape[1], Q.shape[-1])
+    ind[:, bounds[2]:bounds[3]] = 1.0
+    mass2 = oracle.attention(Q, torch.cat(Ks, 1).contiguous(), ind.contiguous())[..., 0].mean()
+    assert abs(mass2 - m_all[2]) < 1e-14
+
+
+def test_query_retrieval_invariants():
+    import torch
+    Q, Ks = _query_setup(2)
+    _, _, base = oracle.score_chunks_query(Q, Ks, 4)
+    # a chunk holding copies of the queries (scaled up) draws almost all the mass
+    Ks2 = list(Ks)
+    Ks2[1] = (Q[:, :7] * 4.0).contiguous()
+    ids, m_sel, m_all = oracle.score_chunks_query(Q, Ks2, 1)
+    assert ids[0] == 1 and m_all[1] > 0.5
+    # duplicating a chunk under a new id: both copies get the same mass, the lower id ranks first
+    Ks3 = Ks + [Ks[2].clone()]
+    ids, _, m3 = oracle.score_chunks_query(Q, Ks3, 5)
+    assert abs(m3[2] - m3[4]) < 1e-15 and list(ids).index(2) < list(ids).index(4)
+    # one candidate: mass 1; R > M; empty store
+    ids, m_sel, m_all = oracle.score_chunks_query(Q, Ks[:1], 3)
+    assert list(ids) == [0] and abs(m_all[0] - 1.0) < 1e-14
+    ids, _, _ = oracle.score_chunks_query(Q, [], 3)
+    assert ids.size == 0
+    # adding a constant vector to every key of every chunk changes nothing
+    c = torch.tensor([0.5, -1.0] * 4)
+    Ks4 = [((k * 64).round() / 64) for k in Ks]
+    _, _, a = oracle.score_chunks_query(Q, Ks4, 4)
+    _, _, b = oracle.score_chunks_query(Q, [(k + c).contiguous() for k in Ks4], 4)
+    np.testing.assert_allclose(a, b, atol=1e-13)
