@@ -206,6 +206,27 @@ def main():
         "gather_hbm_GBps": gather_bytes / (per_call["gather_hbm"] * 1e-3) / 1e9,
     }
 
+    if cfg.M > 0 and cfg.M <= wk.WK_QUERY_MAX_CHUNKS:
+        # query-based retrieval (Sec. 4.2, App. C) in place of the pose distance: attention mass of the
+        # current queries on every stored chunk, over a device-resident index of the chunks' anchor keys
+        index_k = store_k[:, :, :cfg.T].contiguous()
+        index = wk.Store([index_k[c] for c in range(cfg.M)], [index_k[c] for c in range(cfg.M)])
+        n_rows = cfg.H * cfg.N_q
+        lse_c = torch.empty((cfg.M, n_rows), dtype=torch.float32, device=dev)
+        q_ids = torch.empty(cfg.R, dtype=torch.int32, device=dev)
+        q_nf = torch.empty(1, dtype=torch.int32, device=dev)
+        q_ws = torch.empty(wk.wk_score_chunks_query_workspace_bytes(cfg.M, n_rows), dtype=torch.uint8, device=dev)
+        t_lse = time_call(lambda: wk.wk_chunk_lse(index.desc, Q, lse_c), 3)
+        t_top = time_call(lambda: wk.wk_score_chunks_query(lse_c, cfg.M, n_rows, cfg.R, q_ids, None, q_nf, q_ws), 3)
+        q_flops = 2.0 * cfg.N_q * cfg.T * cfg.d * cfg.H * cfg.M
+        extra["query_retrieval"] = {
+            "index": f"anchor keys of all {cfg.M} chunks ({cfg.T} per chunk), HBM-resident",
+            "ms_chunk_lse": t_lse, "ms_score_chunks_query": t_top,
+            "chunk_lse_tflops": q_flops / (t_lse * 1e-3) / 1e12,
+            "chunk_lse_frac_bf16_mfma_peak": q_flops / (t_lse * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        }
+        del index, index_k, lse_c
+
     if not a.no_pinned and cfg.store == "pinned":
         # the CPU-offloaded store of the workload definition: same chunks in pinned host memory
         pk = torch.empty(store_k.shape, dtype=dt, pin_memory=True)

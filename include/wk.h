@@ -137,6 +137,28 @@ wk_status wk_score_chunks(const float *poses, int32_t M, const float *cur_pose, 
                           int32_t R, int32_t *ids_out, double *dist_out, int32_t *n_found,
                           void *hip_stream);
 
+#define WK_QUERY_MAX_CHUNKS 1024
+
+/* Query-based retrieval (Sec. 4.2: the relevance function may be a query-based importance score;
+ * App. C: stored chunks ranked by their attention scores with respect to the current denoising
+ * query).  The relevance of chunk c is the attention mass its keys receive from the current queries
+ * in one softmax over the keys of all M candidate chunks, averaged over all (head, query) rows; the
+ * min(R, M) chunks of largest mass are returned in order of decreasing mass (ties: lower id first).
+ *
+ *   lse        device, [M][n_rows] float: lse[c][r] = natural-log sum over the keys k of chunk c of
+ *              exp(scale * q_r . k) for (head, query) row r -- what wk_chunk_lse writes (or the
+ *              `lse` output of wk_attention run with chunk c's keys as the window, O = NULL)
+ *   ids_out    device out, [R] int32; entries past n_found are -1
+ *   mass_out   device out, [R] double; entries past n_found are -inf.  May be NULL.
+ *   n_found    device out, int32 = min(R, M)
+ *   workspace  device, wk_score_chunks_query_workspace_bytes(M, n_rows) bytes, 256-byte aligned.
+ *              After the call its first M doubles hold the mass of every chunk.
+ * Errors: INVALID_ARG, UNSUPPORTED (M > WK_QUERY_MAX_CHUNKS), WORKSPACE. */
+wk_status wk_score_chunks_query(const float *lse, int32_t M, int64_t n_rows, int32_t R, int32_t *ids_out,
+                                double *mass_out, int32_t *n_found, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+size_t wk_score_chunks_query_workspace_bytes(int32_t M, int64_t n_rows);
+
 /* Pseudo-poses for keyboard/mouse models (Sec. 5.1): accumulate discrete actions into a
  * translation and a rotation.  Labels: 0 W forward, 1 A left, 2 S back, 3 D right, 4 yaw-,
  * 5 yaw+, 6 pitch-, 7 pitch+.  Translation steps of length `step` are taken in the body frame
@@ -182,7 +204,8 @@ wk_status wk_gather_window(const wk_store_desc *store, const int32_t *ids, const
  *
  *   Q          device, [H][N_q][d]
  *   K_win,V_win device, [H][kv_row_stride][d]; the first N_kv rows of each head are attended
- *   O          device out, [H][N_q][d], same element type as the inputs
+ *   O          device out, [H][N_q][d], same element type as the inputs.  May be NULL if lse is
+ *              given: only the log-sum-exp is produced and the value product is skipped.
  *   lse        device out, [H][N_q] float: natural-log sum of exp of the scaled logits. May be NULL.
  *   scale      logit scale; 0 means 1/sqrt(d)
  *   n_kv_dev   device, int32 or NULL.  If given, min(N_kv, *n_kv_dev) keys are attended (the
@@ -201,6 +224,19 @@ wk_status wk_attention(const void *Q, const void *K_win, const void *V_win, void
 
 /* Bytes of workspace with which wk_attention splits the key range for this shape (0: it would not). */
 size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype);
+
+/* First half of query-based retrieval (Sec. 4.2, App. C): the log-sum-exp of the current queries'
+ * scaled logits against the stored keys of every chunk of the store, all chunks in one launch.
+ * The result is the `lse` input of wk_score_chunks_query.  Only K_ptr, n_tok, M, H, d and dtype
+ * of the store are used; the key tables may describe whole compacted chunks or, for a cheaper
+ * index, the anchor-frame keys of each chunk alone.
+ *
+ *   Q          device, [H][N_q][d], element type store->dtype
+ *   scale      logit scale; 0 means 1/sqrt(d)
+ *   lse_out    device out, [M][H][N_q] float; -inf where a chunk holds no token
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, or more than 2^31 workgroups). */
+wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int32_t N_q, float scale,
+                       float *lse_out, void *hip_stream);
 
 /* Device-visible address of a pinned+mapped host allocation (for K_ptr/V_ptr tables and for
  * K_out/V_out of wk_compress_chunk).  Errors: INVALID_ARG, HIP (memory is not pinned). */

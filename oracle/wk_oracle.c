@@ -38,7 +38,11 @@
  *     over candidates (variants: min-max, mean).  Parity with the authors'
  *     normalisation is unpinned;
  *   - rotation = R_y(yaw) * R_x(pitch), no roll; geodesic = rotation angle of
- *     R_cur^T R_i.
+ *     R_cur^T R_i;
+ *   - Eq. 5 does not mention heads: by default a token's key is the concatenation of its
+ *     head slices (one index set per layer); per-head scoring is the variant.  Parity with
+ *     the authors' choice is unpinned (the two modes are pinned to each other by a
+ *     reshaped-input equivalence).
  */
 #include <math.h>
 #include <stdint.h>

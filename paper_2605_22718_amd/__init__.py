@@ -22,9 +22,11 @@ WK_RATIO_CHUNK, WK_RATIO_NONANCHOR = 0, 1
 WK_SCORE_FACTORED, WK_SCORE_GEMM = 0, 1
 WK_NORM_MAX, WK_NORM_MINMAX, WK_NORM_MEAN = 0, 1, 2
 WK_SCORE_MAX_CHUNKS = 4096
+WK_QUERY_MAX_CHUNKS = 1024
 
 EXPORTS = [
     "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
+    "wk_score_chunks_query", "wk_score_chunks_query_workspace_bytes", "wk_chunk_lse",
     "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_attention_workspace_bytes",
     "wk_host_device_pointer",
     "wk_status_string",
@@ -69,12 +71,18 @@ def lib():
                                         vp, C.c_size_t, vp]
         L.wk_score_chunks.restype = C.c_int
         L.wk_score_chunks.argtypes = [vp, i32, C.POINTER(f32), i32, i32, vp, vp, vp, vp]
+        L.wk_score_chunks_query.restype = C.c_int
+        L.wk_score_chunks_query.argtypes = [vp, i32, C.c_int64, i32, vp, vp, vp, vp, C.c_size_t, vp]
+        L.wk_score_chunks_query_workspace_bytes.restype = C.c_size_t
+        L.wk_score_chunks_query_workspace_bytes.argtypes = [i32, C.c_int64]
         L.wk_accumulate_actions.restype = C.c_int
         L.wk_accumulate_actions.argtypes = [vp, i32, f32, f32, f32, vp]
         L.wk_gather_window.restype = C.c_int
         L.wk_gather_window.argtypes = [C.POINTER(wk_store_desc), vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, vp]
         L.wk_attention.restype = C.c_int
         L.wk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, C.c_size_t, vp]
+        L.wk_chunk_lse.restype = C.c_int
+        L.wk_chunk_lse.argtypes = [C.POINTER(wk_store_desc), vp, i32, f32, vp, vp]
         L.wk_attention_workspace_bytes.restype = C.c_size_t
         L.wk_attention_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.wk_host_device_pointer.restype = C.c_int
@@ -167,6 +175,22 @@ def wk_score_chunks(poses, M, cur_pose, norm_mode, R, ids_out, dist_out, n_found
     _check(st, "wk_score_chunks")
 
 
+def wk_score_chunks_query_workspace_bytes(M, n_rows) -> int:
+    return lib().wk_score_chunks_query_workspace_bytes(M, n_rows)
+
+
+def wk_score_chunks_query(lse, M, n_rows, R, ids_out, mass_out, n_found, workspace):
+    """wk_score_chunks_query.  lse: device float32 [M][n_rows]; workspace: device, its first M doubles
+    hold every chunk's mass afterwards."""
+    st = lib().wk_score_chunks_query(_dev(lse, "lse", torch.float32), M, n_rows, R,
+                                     _dev(ids_out, "ids_out", torch.int32),
+                                     _dev(mass_out, "mass_out", torch.float64),
+                                     _dev(n_found, "n_found", torch.int32), _dev(workspace, "workspace"),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _stream())
+    _check(st, "wk_score_chunks_query")
+
+
 def wk_accumulate_actions(labels, step=1.0, dangle=math.radians(15.0), pitch_limit=math.radians(60.0)):
     """wk_accumulate_actions (host).  labels: int32 numpy array or CPU tensor -> float32 CPU tensor [n][5]."""
     lab = torch.as_tensor(labels, dtype=torch.int32).contiguous()
@@ -206,17 +230,27 @@ def wk_gather_window(store_desc: wk_store_desc, ids, n_ids, R_max, K_native, V_n
     _check(st, "wk_gather_window")
 
 
+def wk_chunk_lse(store_desc: wk_store_desc, Q, lse_out, scale=0.0):
+    """wk_chunk_lse.  Q [H][N_q][d]; lse_out device float32 [M][H][N_q]."""
+    st = lib().wk_chunk_lse(C.byref(store_desc), _dev(Q, "Q"), Q.shape[1], scale,
+                            _dev(lse_out, "lse_out", torch.float32), _stream())
+    _check(st, "wk_chunk_lse")
+    return lse_out
+
+
 def wk_attention_workspace_bytes(H, N_q, N_kv, dtype) -> int:
     return lib().wk_attention_workspace_bytes(H, N_q, N_kv, dtype)
 
 
 def wk_attention(Q, K_win, V_win, O, lse=None, N_kv=None, scale=0.0, n_kv_dev=None, workspace=None):
-    """wk_attention.  Q [H][N_q][d]; K_win/V_win [H][stride][d]; O like Q (written in place)."""
+    """wk_attention.  Q [H][N_q][d]; K_win/V_win [H][stride][d]; O like Q (written in place).
+    O = None (then V_win may be None too) asks for lse only."""
     H, N_q, d = Q.shape
     stride = K_win.shape[1]
     N_kv = stride if N_kv is None else N_kv
-    st = lib().wk_attention(_dev(Q, "Q"), _dev(K_win, "K_win", Q.dtype), _dev(V_win, "V_win", Q.dtype),
-                            _dev(O, "O", Q.dtype), _dev(lse, "lse", torch.float32), H, N_q, N_kv, d, stride,
+    st = lib().wk_attention(_dev(Q, "Q"), _dev(K_win, "K_win", Q.dtype),
+                            None if V_win is None else _dev(V_win, "V_win", Q.dtype),
+                            None if O is None else _dev(O, "O", Q.dtype), _dev(lse, "lse", torch.float32), H, N_q, N_kv, d, stride,
                             dtype_code(Q), scale, _dev(n_kv_dev, "n_kv_dev", torch.int32),
                             _dev(workspace, "workspace"),
                             0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())

@@ -40,6 +40,11 @@ struct AttnArgs {
     int splits;        // key-range splits per (head, query tile); 1 = none
     float *part_o;     // splits > 1: [splits][H][N_q][128] unnormalised fp32 partial outputs
     float *part_ml;    //             [splits][H][N_q][2] running max (log2 units) and row sum
+    // batch over stored chunks (log-sum-exp only): chunk c has keys k_table[c] = [H][n_tok[c]][128]
+    // and writes lse + c*H*N_q.  n_chunks = 0: one window, K above.
+    const void *const *k_table;
+    const int32_t *n_tok;
+    int n_chunks;
 };
 
 constexpr int kXcds = 8;
@@ -49,25 +54,46 @@ constexpr int kXcds = 8;
 // [x*per_xcd, (x+1)*per_xcd) keeps the query tiles that stream the same head's K/V on one XCD,
 // so that head's window is fetched from HBM once into that XCD's L2 instead of once per tile.
 // With a split key range the items of one head are ordered split-major, so the query tiles that
-// stream the same slice of K/V stay neighbours.
-__device__ inline bool work_item(const AttnArgs &a, int &h, int &qt, int &sp) {
+// stream the same slice of K/V stay neighbours.  A batch over stored chunks is chunk-major.
+__device__ inline bool work_item(const AttnArgs &a, int &c, int &h, int &qt, int &sp) {
     const int lin = blockIdx.x;
+    const int per_chunk = a.H * a.n_qtiles * a.splits;
     const int w = (lin % kXcds) * a.per_xcd + lin / kXcds;
-    if (lin / kXcds >= a.per_xcd || w >= a.H * a.n_qtiles * a.splits) return false;
-    h = w / (a.n_qtiles * a.splits);
-    const int rem = w % (a.n_qtiles * a.splits);
+    if (lin / kXcds >= a.per_xcd || w >= per_chunk * (a.n_chunks > 0 ? a.n_chunks : 1)) return false;
+    c = w / per_chunk;
+    const int wc = w % per_chunk;
+    h = wc / (a.n_qtiles * a.splits);
+    const int rem = wc % (a.n_qtiles * a.splits);
     sp = rem / a.n_qtiles;
     qt = rem % a.n_qtiles;
     return true;
 }
 
-__device__ inline int window_length(const AttnArgs &a) {
-    int n = a.N_kv;
-    if (a.n_kv_dev) {
-        const int m = *a.n_kv_dev;
-        n = m < n ? m : n;
+// The window this workgroup reads: its keys, row stride between heads and length; where lse goes.
+struct Window {
+    const char *K;
+    float *lse;
+    int stride, n_kv;
+};
+
+__device__ inline Window window_of(const AttnArgs &a, int c) {
+    Window w;
+    if (a.n_chunks > 0) {
+        w.K = reinterpret_cast<const char *>(a.k_table[c]);
+        w.n_kv = w.stride = a.n_tok[c];
+        w.lse = a.lse + (size_t)c * a.H * a.N_q;
+    } else {
+        w.K = a.K;
+        w.stride = a.kv_row_stride;
+        w.lse = a.lse;
+        w.n_kv = a.N_kv;
+        if (a.n_kv_dev) {
+            const int m = *a.n_kv_dev;
+            w.n_kv = m < w.n_kv ? m : w.n_kv;
+        }
     }
-    return n < 0 ? 0 : n;
+    if (w.n_kv < 0) w.n_kv = 0;
+    return w;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -81,9 +107,11 @@ constexpr int kF32VPitch = WK_D + 8;  // rows 4 apart land 32 banks apart
 __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
     __shared__ float Ks[kF32Keys * kF32KPitch];
     __shared__ float Vs[kF32Keys * kF32VPitch];
-    int h, qt, sp;
-    if (!work_item(a, h, qt, sp)) return;
-    const int n_kv = window_length(a);
+    int c, h, qt, sp;
+    if (!work_item(a, c, h, qt, sp)) return;
+    const Window win = window_of(a, c);
+    const int n_kv = win.n_kv;
+    float *const lse = win.lse;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int q = qt * (kF32Waves * 32) + wave * 32 + col;
@@ -91,11 +119,13 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
     const int q_ld = q_ok ? q : a.N_q - 1;
     const float *Qrow = reinterpret_cast<const float *>(a.Q) + ((size_t)h * a.N_q + q_ld) * WK_D;
     float *Orow = reinterpret_cast<float *>(a.O) + ((size_t)h * a.N_q + q_ld) * WK_D;
+    const bool with_o = a.O != nullptr;   // false: log-sum-exp only, V is not read (zeros stand in)
 
     if (n_kv == 0) {
         if (q_ok) {
-            for (int c = g * 64; c < g * 64 + 64; c += 4) *reinterpret_cast<float4 *>(Orow + c) = float4{0, 0, 0, 0};
-            if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = -INFINITY;
+            if (with_o)
+                for (int c = g * 64; c < g * 64 + 64; c += 4) *reinterpret_cast<float4 *>(Orow + c) = float4{0, 0, 0, 0};
+            if (lse && g == 0) lse[(size_t)h * a.N_q + q] = -INFINITY;
         }
         return;
     }
@@ -112,8 +142,8 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
         for (int r = 0; r < 16; ++r) o[b][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    const float *Kh = reinterpret_cast<const float *>(a.K) + (size_t)h * a.kv_row_stride * WK_D;
-    const float *Vh = reinterpret_cast<const float *>(a.V) + (size_t)h * a.kv_row_stride * WK_D;
+    const float *Kh = reinterpret_cast<const float *>(win.K) + (size_t)h * win.stride * WK_D;
+    const float *Vh = reinterpret_cast<const float *>(a.V) + (size_t)h * win.stride * WK_D;
 
     for (int kt = 0; kt < n_kv; kt += kF32Keys) {
         __syncthreads();  // previous tile fully consumed
@@ -124,7 +154,7 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
             float4 kv = float4{0, 0, 0, 0}, vv = float4{0, 0, 0, 0};
             if (kt + row < n_kv) {
                 kv = *reinterpret_cast<const float4 *>(Kh + (size_t)(kt + row) * WK_D + 4 * c4);
-                vv = *reinterpret_cast<const float4 *>(Vh + (size_t)(kt + row) * WK_D + 4 * c4);
+                if (with_o) vv = *reinterpret_cast<const float4 *>(Vh + (size_t)(kt + row) * WK_D + 4 * c4);
             }
             *reinterpret_cast<float4 *>(&Ks[row * kF32KPitch + 4 * c4]) = kv;
             *reinterpret_cast<float4 *>(&Vs[row * kF32VPitch + 4 * c4]) = vv;
@@ -179,6 +209,7 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (q_ok) {
         const float inv = 1.f / l_tot;
+        if (with_o)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -187,7 +218,7 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
                 *reinterpret_cast<float4 *>(Orow + dv) =
                     float4{o[b][4 * t] * inv, o[b][4 * t + 1] * inv, o[b][4 * t + 2] * inv, o[b][4 * t + 3] * inv};
             }
-        if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        if (lse && g == 0) lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 
@@ -222,13 +253,19 @@ __device__ inline float max_across_halves(float x) {
 #define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
-template <int WAVES>
+// WITH_O = false: only the log-sum-exp is wanted (a.O is NULL, one key range).  The V tiles are
+// neither loaded nor multiplied; the row sums are formed exactly as in the full kernel.
+template <int WAVES, bool WITH_O>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
+    // s_waitcnt that lets one tile's loads of this wave (4 with V, 2 without) stay in flight
+    constexpr int kWaitOneTile = WITH_O ? 0x0F74 : 0x0F72;
     extern __shared__ __attribute__((aligned(256))) char smem[];
-    int h, qt, sp;
-    if (!work_item(a, h, qt, sp)) return;
-    const int n_kv = window_length(a);
+    int c, h, qt, sp;
+    if (!work_item(a, c, h, qt, sp)) return;
+    const Window win = window_of(a, c);
+    const int n_kv = win.n_kv;
+    float *const lse = win.lse;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
@@ -245,9 +282,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     if (t0 >= t1) {   // empty window, or a split past its end: contributes nothing
         if (q_ok) {
             if (a.splits == 1) {
-                char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
-                for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
-                if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = -INFINITY;
+                if constexpr (WITH_O) {
+                    char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+                    for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
+                }
+                if (lse && g == 0) lse[(size_t)h * a.N_q + q] = -INFINITY;
             } else {
                 const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
                 for (int c = g * 16; c < g * 16 + 16; ++c) reinterpret_cast<float4 *>(a.part_o + row * WK_D)[c] = float4{0, 0, 0, 0};
@@ -293,8 +332,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
             v_src[i] = R * 256 + ((p ^ (r << 2)) << 4);
         }
     }
-    const char *Kh = a.K + (size_t)h * a.kv_row_stride * 256;
-    const char *Vh = a.V + (size_t)h * a.kv_row_stride * 256;
+    const char *Kh = win.K + (size_t)h * win.stride * 256;
+    const char *Vh = a.V + (size_t)h * win.stride * 256;
     const unsigned last_off = (unsigned)(n_kv - 1) * 256u;
     char *const dma_dst = smem + wave * 2048;   // + slot*16384 (+ kVRing) + i*1024
 
@@ -307,7 +346,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + (t_off + k_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+                if constexpr (WITH_O)
+                    __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
             }
         } else {
 #pragma unroll
@@ -315,7 +355,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                 const unsigned ko = min(t_off + k_src[i], last_off + (k_src[i] & 255u));
                 const unsigned vo = min(t_off + v_src[i], last_off + (v_src[i] & 255u));
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + ko), WK_LDS(dst + i * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+                if constexpr (WITH_O)
+                    __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
             }
         }
     };
@@ -361,10 +402,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             l_run *= alpha;
+            if constexpr (WITH_O) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+                    for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
+            }
         }
     };
     // p = exp2(s*c - m) rounded to bf16; registers 8*t2 .. 8*t2+7 of block b -> k step 2*b + t2.
@@ -387,6 +430,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                 }
     };
     auto accumulate_pv = [&](int byte_off, const bf16x8 (&pb)[4]) {
+        if constexpr (!WITH_O) return;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -406,7 +450,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     issue_tile(t0, sh);
     issue_tile(t0 + 1, (sh + 1) & 3);
     issue_tile(t0 + 2, (sh + 2) & 3);
-    __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tiles 0 and 1 of this wave have landed
+    __builtin_amdgcn_s_waitcnt(kWaitOneTile);   // tiles 0 and 1 of this wave have landed
     __syncthreads();
     f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
     float mt;
@@ -423,7 +467,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
         probabilities(s_cur, pb);
         accumulate_pv(POS * kTileBytes, pb);
         mt = tile_max(s_next);
-        __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): everything but tile j+3 has landed
+        __builtin_amdgcn_s_waitcnt(kWaitOneTile);   // everything but tile j+3 has landed
         __syncthreads();
     };
     using P0 = std::integral_constant<int, 0>;
@@ -465,22 +509,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (q_ok && a.splits == 1) {
-        char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
-        const float inv = 1.f / l_tot;
+        if constexpr (WITH_O) {
+            char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+            const float inv = 1.f / l_tot;
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int dv = 32 * b + 8 * t + 4 * g;
-                const bf16x2 lo = __builtin_convertvector(f32x2{o[b][4 * t] * inv, o[b][4 * t + 1] * inv}, bf16x2);
-                const bf16x2 hi = __builtin_convertvector(f32x2{o[b][4 * t + 2] * inv, o[b][4 * t + 3] * inv}, bf16x2);
-                uint2 w;
-                w.x = __builtin_bit_cast(uint32_t, lo);
-                w.y = __builtin_bit_cast(uint32_t, hi);
-                *reinterpret_cast<uint2 *>(Orow + dv * 2) = w;
-            }
-        if (a.lse && g == 0) a.lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
-    } else if (q_ok) {   // partial result of this key range, merged by k_attn_merge
+                for (int t = 0; t < 4; ++t) {
+                    const int dv = 32 * b + 8 * t + 4 * g;
+                    const bf16x2 lo = __builtin_convertvector(f32x2{o[b][4 * t] * inv, o[b][4 * t + 1] * inv}, bf16x2);
+                    const bf16x2 hi = __builtin_convertvector(f32x2{o[b][4 * t + 2] * inv, o[b][4 * t + 3] * inv}, bf16x2);
+                    uint2 w;
+                    w.x = __builtin_bit_cast(uint32_t, lo);
+                    w.y = __builtin_bit_cast(uint32_t, hi);
+                    *reinterpret_cast<uint2 *>(Orow + dv * 2) = w;
+                }
+        }
+        if (lse && g == 0) lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+    } else if (WITH_O && q_ok) {   // partial result of this key range, merged by k_attn_merge
         const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
         float *Po = a.part_o + row * WK_D;
 #pragma unroll
@@ -546,23 +592,28 @@ template <int WAVES>
 wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipStream_t st) {
     const int q_per_wg = WAVES * 32;
     a.n_qtiles = (a.N_q + q_per_wg - 1) / q_per_wg;
-    a.splits = choose_splits(a.H * a.n_qtiles, (a.N_kv + kKeys - 1) / kKeys);
+    a.splits = a.O && a.n_chunks == 0 ? choose_splits(a.H * a.n_qtiles, (a.N_kv + kKeys - 1) / kKeys) : 1;
     if (a.splits > 1 && (!workspace || workspace_bytes < split_workspace_bytes(a.H, a.N_q, a.splits) ||
                          reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
         a.splits = 1;   // no room for partial results: one workgroup walks the whole window
     a.part_o = reinterpret_cast<float *>(workspace);
     a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
                                           wk::align_up((size_t)a.splits * a.H * a.N_q * WK_D * sizeof(float), 256));
-    const int items = a.H * a.n_qtiles * a.splits;
+    const int items = a.H * a.n_qtiles * a.splits * (a.n_chunks > 0 ? a.n_chunks : 1);
     a.per_xcd = (items + kXcds - 1) / kXcds;
     static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
     if (!lds_limit_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
             return WK_ERR_HIP;
         lds_limit_set = true;
     }
-    hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
+    if (a.O)
+        hipLaunchKernelGGL((k_attn_bf16<WAVES, true>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
+    else
+        hipLaunchKernelGGL((k_attn_bf16<WAVES, false>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
     WK_LAUNCH_CHECK();
     if (a.splits > 1) {
         const size_t rows = (size_t)a.H * a.N_q;
@@ -578,7 +629,8 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
                                   int32_t H, int32_t N_q, int32_t N_kv, int32_t d, int32_t kv_row_stride,
                                   int32_t dtype, float scale, const int32_t *n_kv_dev, void *workspace,
                                   size_t workspace_bytes, void *hip_stream) {
-    if (!Q || !K_win || !V_win || !O) return WK_ERR_INVALID_ARG;
+    if (!Q || !K_win) return WK_ERR_INVALID_ARG;
+    if (O ? !V_win : !lse) return WK_ERR_INVALID_ARG;   // O == NULL: log-sum-exp only, V is not read
     if (H < 1 || N_q < 0 || d < 1) return WK_ERR_INVALID_ARG;
     if (dtype != WK_F32 && dtype != WK_BF16) return WK_ERR_INVALID_ARG;
     if (!(scale >= 0.f) || std::isinf(scale)) return WK_ERR_INVALID_ARG;
@@ -598,6 +650,9 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     a.splits = 1;
     a.part_o = nullptr;
     a.part_ml = nullptr;
+    a.k_table = nullptr;
+    a.n_tok = nullptr;
+    a.n_chunks = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     if (dtype == WK_F32) {
         const int q_per_wg = kF32Waves * 32;
@@ -609,6 +664,44 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
         return WK_OK;
     }
     return launch_bf16<8>(a, workspace, workspace_bytes, st);
+}
+
+extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int32_t N_q, float scale,
+                                  float *lse_out, void *hip_stream) {
+    if (!store || !Q || !lse_out) return WK_ERR_INVALID_ARG;
+    if (store->M < 0 || store->H < 1 || N_q < 0 || store->max_tok < 0) return WK_ERR_INVALID_ARG;
+    if (store->dtype != WK_F32 && store->dtype != WK_BF16) return WK_ERR_INVALID_ARG;
+    if (!(scale >= 0.f) || std::isinf(scale)) return WK_ERR_INVALID_ARG;
+    if (store->d != WK_D) return WK_ERR_UNSUPPORTED;
+    if (store->M == 0 || N_q == 0) return WK_OK;
+    if (!store->K_ptr || !store->n_tok) return WK_ERR_INVALID_ARG;
+    AttnArgs a;
+    a.Q = reinterpret_cast<const char *>(Q);
+    a.K = a.V = nullptr;
+    a.O = nullptr;
+    a.lse = lse_out;
+    a.H = store->H; a.N_q = N_q; a.N_kv = 0; a.kv_row_stride = 0;
+    const float sc = scale == 0.f ? 1.f / std::sqrt((float)WK_D) : scale;
+    a.scale_log2 = sc * 1.4426950408889634f;
+    a.n_kv_dev = nullptr;
+    a.splits = 1;
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
+    a.k_table = store->K_ptr;
+    a.n_tok = store->n_tok;
+    a.n_chunks = store->M;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int q_per_wg = (store->dtype == WK_F32 ? kF32Waves : 8) * 32;
+    const long long items = (long long)store->M * store->H * ((N_q + q_per_wg - 1) / q_per_wg);
+    if (items + kXcds > 0x7fffffffLL) return WK_ERR_UNSUPPORTED;
+    if (store->dtype == WK_F32) {
+        a.n_qtiles = (N_q + q_per_wg - 1) / q_per_wg;
+        a.per_xcd = (int)((items + kXcds - 1) / kXcds);
+        hipLaunchKernelGGL(k_attn_f32, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a);
+        WK_LAUNCH_CHECK();
+        return WK_OK;
+    }
+    return launch_bf16<8>(a, nullptr, 0, st);
 }
 
 extern "C" size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype) {

@@ -145,6 +145,125 @@ extern "C" wk_status wk_score_chunks(const float *poses, int32_t M, const float 
     return WK_OK;
 }
 
+// ---- query-based retrieval (paper Sec. 4.2, App. C) -------------------------------------------------
+//
+// Input: lse[c][r] = log sum_k exp(q_r . k / sqrt(d)) over the keys k of stored chunk c, for every
+// (head, query) row r -- what wk_attention writes as `lse` when run over one chunk.  In a softmax
+// over the keys of all M chunks, chunk c receives mass exp(lse[c][r] - logsumexp_c' lse[c'][r]) from
+// row r; the relevance of a chunk is the mean of that mass over the rows.  fp64 throughout.
+namespace {
+
+constexpr int kQThreads = 256;
+
+__global__ __launch_bounds__(kQThreads) void k_query_mass_partial(const float *__restrict__ lse, int M,
+                                                                  long long n_rows, double *__restrict__ partial) {
+    __shared__ double acc[kQThreads / 64][WK_QUERY_MAX_CHUNKS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int c = lane; c < M; c += 64) acc[wave][c] = 0.0;
+    // (each wave only touches its own row of acc: no barrier needed until the end)
+    for (long long r0 = (long long)blockIdx.x * kQThreads; r0 < n_rows; r0 += (long long)gridDim.x * kQThreads) {
+        const long long r = r0 + tid;
+        const bool ok = r < n_rows;
+        double mx = -INFINITY;
+        if (ok)
+            for (int c = 0; c < M; ++c) mx = fmax(mx, (double)lse[(size_t)c * n_rows + r]);
+        double sum = 0.0;
+        if (ok && mx > -INFINITY)
+            for (int c = 0; c < M; ++c) sum += exp((double)lse[(size_t)c * n_rows + r] - mx);
+        const double L = mx + log(sum);   // -inf or NaN for rows that see no key at all: they are skipped
+        for (int c = 0; c < M; ++c) {
+            double w = 0.0;
+            if (ok && sum > 0.0) w = exp((double)lse[(size_t)c * n_rows + r] - L);
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) w += __shfl_xor(w, o);
+            if (lane == 0) acc[wave][c] += w;
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < M; c += kQThreads) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kQThreads / 64; ++w) s += acc[w][c];
+        partial[(size_t)blockIdx.x * M + c] = s;
+    }
+}
+
+// mass[c] = sum of the blocks' partial sums / n_rows; the min(R, M) largest, ties to the lower id
+__global__ __launch_bounds__(kThreads) void k_query_topk(const double *__restrict__ partial, int n_blocks, int M,
+                                                         long long n_rows, int R, double *__restrict__ mass_all,
+                                                         int32_t *__restrict__ ids_out,
+                                                         double *__restrict__ mass_out,
+                                                         int32_t *__restrict__ n_found) {
+    __shared__ double mass[WK_QUERY_MAX_CHUNKS];
+    const int tid = threadIdx.x;
+    const int found = R < M ? R : M;
+    if (tid == 0) *n_found = found;
+    for (int r = found + tid; r < R; r += kThreads) {
+        ids_out[r] = -1;
+        if (mass_out) mass_out[r] = -INFINITY;
+    }
+    if (M == 0) return;
+    for (int c = tid; c < M; c += kThreads) {
+        double s = 0.0;
+        for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * M + c];
+        s /= (double)n_rows;
+        mass[c] = s;
+        mass_all[c] = s;
+    }
+    __syncthreads();
+    for (int c = tid; c < M; c += kThreads) {
+        const double mc = mass[c];
+        int rank = 0;
+        for (int j = 0; j < M; ++j) {
+            const double mj = mass[j];
+            rank += (mj > mc || (mj == mc && j < c)) ? 1 : 0;
+        }
+        if (rank < found) {
+            ids_out[rank] = c;
+            if (mass_out) mass_out[rank] = mc;
+        }
+    }
+}
+
+int query_blocks(long long n_rows) {
+    const long long b = (n_rows + kQThreads - 1) / kQThreads;
+    return (int)(b < 1 ? 1 : (b > 1024 ? 1024 : b));
+}
+
+}  // namespace
+
+extern "C" size_t wk_score_chunks_query_workspace_bytes(int32_t M, int64_t n_rows) {
+    if (M < 0 || M > WK_QUERY_MAX_CHUNKS || n_rows < 1) return 0;
+    const size_t m = (size_t)(M > 0 ? M : 1);
+    return wk::align_up(m * sizeof(double), 256) + wk::align_up((size_t)query_blocks(n_rows) * m * sizeof(double), 256);
+}
+
+extern "C" wk_status wk_score_chunks_query(const float *lse, int32_t M, int64_t n_rows, int32_t R, int32_t *ids_out,
+                                           double *mass_out, int32_t *n_found, void *workspace,
+                                           size_t workspace_bytes, void *hip_stream) {
+    if (M < 0 || R < 0 || n_rows < 1 || !n_found) return WK_ERR_INVALID_ARG;
+    if (M > 0 && !lse) return WK_ERR_INVALID_ARG;
+    if (R > 0 && !ids_out) return WK_ERR_INVALID_ARG;
+    if (M > WK_QUERY_MAX_CHUNKS) return WK_ERR_UNSUPPORTED;
+    const size_t need = wk_score_chunks_query_workspace_bytes(M, n_rows);
+    if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return WK_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    double *mass_all = reinterpret_cast<double *>(workspace);
+    double *partial = reinterpret_cast<double *>(reinterpret_cast<char *>(workspace) +
+                                                 wk::align_up((size_t)(M > 0 ? M : 1) * sizeof(double), 256));
+    const int nb = query_blocks(n_rows);
+    if (M > 0) {
+        hipLaunchKernelGGL(k_query_mass_partial, dim3(nb), dim3(kQThreads), 0, st, lse, (int)M, (long long)n_rows,
+                           partial);
+        WK_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_query_topk, dim3(1), dim3(kThreads), 0, st, partial, nb, (int)M, (long long)n_rows, (int)R,
+                       mass_all, ids_out, mass_out, n_found);
+    WK_LAUNCH_CHECK();
+    return WK_OK;
+}
+
 extern "C" wk_status wk_accumulate_actions(const int32_t *labels, int32_t n, float step, float dangle,
                                            float pitch_limit, float *poses_out) {
     if (n < 0 || (n > 0 && (!labels || !poses_out))) return WK_ERR_INVALID_ARG;

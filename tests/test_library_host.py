@@ -110,6 +110,35 @@ def test_argument_validation_of_the_other_calls():
     assert attn(dtype=5) == wk.WK_ERR_INVALID_ARG
     assert attn(H=0) == wk.WK_ERR_INVALID_ARG
     assert L.wk_attention(None, one, one, one, None, 2, 8, 8, 128, 8, 1, 0.0, None, None, 0, None) == wk.WK_ERR_INVALID_ARG
+    # O == NULL asks for the log-sum-exp only and then needs lse
+    assert L.wk_attention(one, one, None, None, None, 2, 8, 8, 128, 8, 1, 0.0, None, None, 0, None) == wk.WK_ERR_INVALID_ARG
+    # query-based retrieval
+    assert wk.wk_score_chunks_query_workspace_bytes(wk.WK_QUERY_MAX_CHUNKS + 1, 100) == 0
+    need = wk.wk_score_chunks_query_workspace_bytes(120, 40 * 4680)
+    assert need >= 120 * 8 * 2 and need % 256 == 0
+    def sq(**kw):
+        a = dict(dict(lse=one, M=4, n_rows=64, R=2, ids=one, n_found=one, ws=one, ws_bytes=1 << 20), **kw)
+        return L.wk_score_chunks_query(a["lse"], a["M"], a["n_rows"], a["R"], a["ids"], None, a["n_found"],
+                                       a["ws"], a["ws_bytes"], None)
+    assert sq(M=-1) == wk.WK_ERR_INVALID_ARG
+    assert sq(n_rows=0) == wk.WK_ERR_INVALID_ARG
+    assert sq(lse=None) == wk.WK_ERR_INVALID_ARG
+    assert sq(ids=None) == wk.WK_ERR_INVALID_ARG
+    assert sq(n_found=None) == wk.WK_ERR_INVALID_ARG
+    assert sq(M=wk.WK_QUERY_MAX_CHUNKS + 1) == wk.WK_ERR_UNSUPPORTED
+    assert sq(ws=None) == wk.WK_ERR_WORKSPACE
+    assert sq(ws_bytes=16) == wk.WK_ERR_WORKSPACE
+    assert sq(ws=C.c_void_p(264)) == wk.WK_ERR_WORKSPACE
+    sd = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 128, wk.WK_BF16)
+    assert L.wk_chunk_lse(None, one, 8, 0.0, one, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_chunk_lse(C.byref(sd), None, 8, 0.0, one, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_chunk_lse(C.byref(sd), one, 8, 0.0, None, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_chunk_lse(C.byref(sd), one, -1, 0.0, one, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_chunk_lse(C.byref(sd), one, 8, -1.0, one, None) == wk.WK_ERR_INVALID_ARG
+    sd64 = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 64, wk.WK_BF16)
+    assert L.wk_chunk_lse(C.byref(sd64), one, 8, 0.0, one, None) == wk.WK_ERR_UNSUPPORTED
+    sd0 = wk.wk_store_desc(None, None, None, 0, 0, 2, 128, wk.WK_BF16)
+    assert L.wk_chunk_lse(C.byref(sd0), one, 8, 0.0, one, None) == wk.WK_OK      # empty store: nothing to do
     # key-range splits are only proposed when the plain grid would leave compute units idle
     assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
     assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4

@@ -18,6 +18,7 @@ from .generators import (
     make_queries,
     make_native,
     make_chunk,
+    make_revisit_keys,
     make_poses,
     make_action_labels,
     torch_dtype,
@@ -32,6 +33,7 @@ __all__ = [
     "make_queries",
     "make_native",
     "make_chunk",
+    "make_revisit_keys",
     "make_poses",
     "make_action_labels",
     "torch_dtype",

@@ -91,6 +91,7 @@ def normal(seed: int, stream, shape, device="cpu", block: int = 1 << 24) -> torc
 _S_Q, _S_NATK, _S_NATV = 1, 2, 3
 _S_ANCK, _S_ANCV, _S_FRK, _S_FRV, _S_NOK, _S_NOV, _S_MASK = 10, 11, 12, 13, 14, 15, 16
 _S_POSE, _S_ACT = 20, 21
+_S_REVK, _S_REVA = 30, 31
 
 
 def make_queries(cfg: WkConfig, device="cpu", n_q=None) -> torch.Tensor:
@@ -137,6 +138,25 @@ def make_chunk(cfg: WkConfig, chunk_id: int, device="cpu", sigma: float = 0.05, 
     V = torch.cat(frames_v, dim=1).to(dt).contiguous()
     K_anchor = anc_k.to(dt).contiguous() if external else None
     return K, V, K_anchor
+
+
+def make_revisit_keys(cfg: WkConfig, Q: torch.Tensor, lens, device="cpu"):
+    """Stored key chunks for query-based retrieval, some of which "see" what the current queries see.
+
+    Chunk c has lens[c] keys per head: N(0,1) noise plus a_c times a query row (row (7*j + c) mod N_q
+    for key j), with a_c drawn uniformly from [0, 0.6] per chunk -- a revisited viewpoint has keys
+    aligned with the current queries (a_c large), an unrelated one has not (a_c near 0).  Returns the
+    list of [H][lens[c]][d] tensors in the config dtype and the numpy array of the a_c.
+    """
+    H, N_q, d = Q.shape
+    a = uniform(cfg.seed, _S_REVA, (len(lens),), "cpu").double().numpy() * 0.6
+    out = []
+    Qf = Q.to(device=device, dtype=torch.float32)
+    for c, n in enumerate(lens):
+        rows = (7 * torch.arange(n, device=device) + c) % N_q
+        k = normal(cfg.seed, (_S_REVK, c), (H, n, d), device) + float(a[c]) * Qf[:, rows]
+        out.append(k.to(torch_dtype(cfg.dtype)).contiguous())
+    return out, a
 
 
 def make_poses(M: int, seed: int):
