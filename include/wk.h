@@ -238,6 +238,54 @@ size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_
 wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int32_t N_q, float scale,
                        float *lse_out, void *hip_stream);
 
+/* ---- Overlap of a CPU-offloaded store with attention (Sec. 7: the host-to-device transfer at
+ * retrieval time is the stated obstacle to real time with all KV chunks in CPU memory).
+ *
+ * A wk_prefetch owns one extra HIP stream of default priority (the "copy stream") and, per window
+ * buffer ("slot", at most 8), two events.  The intended loop over the layers l of a denoising step,
+ * with two window buffers and the ids of wk_score_chunks (the same for every layer):
+ *
+ *     wk_prefetch_after(p, compute)                         ids/n_found are ready before any gather
+ *     wk_prefetch_gather(p, 0, store[0], ..., win[0], ...)
+ *     for l = 0 .. L-1:
+ *         if l+1 < L: wk_prefetch_gather(p, (l+1)%2, store[l+1], ..., win[(l+1)%2], ...)
+ *         wk_prefetch_acquire(p, l%2, compute)
+ *         wk_attention(Q[l], win[l%2], ..., compute)
+ *         wk_prefetch_release(p, l%2, compute)
+ *
+ * so that the assembly of layer l+1's window (host-link-bound when the store is in pinned host
+ * memory) runs while layer l attends.  The same stream serves the other direction: after
+ * wk_prefetch_after(p, compute), wk_compress_chunk(..., wk_prefetch_stream(p)) with K_out/V_out in
+ * mapped host memory writes an evicted chunk to the CPU-side store without stalling the compute
+ * stream.  Calls on one wk_prefetch must come from one host thread at a time.  Nothing here
+ * synchronises the host except wk_prefetch_destroy. */
+typedef struct wk_prefetch wk_prefetch;
+
+/* Creates the copy stream and 2*n_slots events on the current device.  Errors: INVALID_ARG
+ * (n_slots outside 1..8), HIP. */
+wk_status wk_prefetch_create(wk_prefetch **out, int32_t n_slots);
+/* Waits for the copy stream to drain, then frees stream and events.  NULL is allowed. */
+wk_status wk_prefetch_destroy(wk_prefetch *p);
+/* The copy stream (a hipStream_t), for enqueueing other transfers in order with the gathers. */
+void *wk_prefetch_stream(wk_prefetch *p);
+/* Work enqueued on the copy stream from now on starts only after everything enqueued so far on
+ * hip_stream has finished. */
+wk_status wk_prefetch_after(wk_prefetch *p, void *hip_stream);
+/* wk_gather_window (same arguments, same errors) on the copy stream into the window buffers of
+ * `slot`: first waits until the consumers recorded by the last wk_prefetch_release of that slot
+ * have finished, afterwards marks the slot ready.  max_workgroups > 0 caps the grid (a host-link
+ * bound gather needs only a few workgroups in flight; 0 = one workgroup per 32 KB). */
+wk_status wk_prefetch_gather(wk_prefetch *p, int32_t slot, const wk_store_desc *store, const int32_t *ids,
+                             const int32_t *n_ids, int32_t R_max, const void *K_native,
+                             const void *V_native, int32_t n_native, void *K_win, void *V_win,
+                             int32_t win_capacity, int32_t *n_win, int32_t max_workgroups);
+/* Work enqueued on hip_stream from now on starts only after the slot's last gather has finished.
+ * Errors: INVALID_ARG (no gather was enqueued for this slot yet), HIP. */
+wk_status wk_prefetch_acquire(wk_prefetch *p, int32_t slot, void *hip_stream);
+/* Declares that every reader of the slot's window has been enqueued on hip_stream: the next gather
+ * into the slot waits for them. */
+wk_status wk_prefetch_release(wk_prefetch *p, int32_t slot, void *hip_stream);
+
 /* Device-visible address of a pinned+mapped host allocation (for K_ptr/V_ptr tables and for
  * K_out/V_out of wk_compress_chunk).  Errors: INVALID_ARG, HIP (memory is not pinned). */
 wk_status wk_host_device_pointer(void *host_ptr, void **device_ptr);

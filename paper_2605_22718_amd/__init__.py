@@ -27,6 +27,8 @@ WK_QUERY_MAX_CHUNKS = 1024
 EXPORTS = [
     "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
     "wk_score_chunks_query", "wk_score_chunks_query_workspace_bytes", "wk_chunk_lse",
+    "wk_prefetch_create", "wk_prefetch_destroy", "wk_prefetch_stream", "wk_prefetch_after", "wk_prefetch_gather",
+    "wk_prefetch_acquire", "wk_prefetch_release",
     "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_attention_workspace_bytes",
     "wk_host_device_pointer",
     "wk_status_string",
@@ -83,6 +85,21 @@ def lib():
         L.wk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, C.c_size_t, vp]
         L.wk_chunk_lse.restype = C.c_int
         L.wk_chunk_lse.argtypes = [C.POINTER(wk_store_desc), vp, i32, f32, vp, vp]
+        L.wk_prefetch_create.restype = C.c_int
+        L.wk_prefetch_create.argtypes = [C.POINTER(vp), i32]
+        L.wk_prefetch_destroy.restype = C.c_int
+        L.wk_prefetch_destroy.argtypes = [vp]
+        L.wk_prefetch_stream.restype = vp
+        L.wk_prefetch_stream.argtypes = [vp]
+        L.wk_prefetch_after.restype = C.c_int
+        L.wk_prefetch_after.argtypes = [vp, vp]
+        L.wk_prefetch_gather.restype = C.c_int
+        L.wk_prefetch_gather.argtypes = [vp, i32, C.POINTER(wk_store_desc), vp, vp, i32, vp, vp, i32, vp, vp, i32, vp,
+                                         i32]
+        L.wk_prefetch_acquire.restype = C.c_int
+        L.wk_prefetch_acquire.argtypes = [vp, i32, vp]
+        L.wk_prefetch_release.restype = C.c_int
+        L.wk_prefetch_release.argtypes = [vp, i32, vp]
         L.wk_attention_workspace_bytes.restype = C.c_size_t
         L.wk_attention_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.wk_host_device_pointer.restype = C.c_int
@@ -236,6 +253,43 @@ def wk_chunk_lse(store_desc: wk_store_desc, Q, lse_out, scale=0.0):
                             _dev(lse_out, "lse_out", torch.float32), _stream())
     _check(st, "wk_chunk_lse")
     return lse_out
+
+
+def wk_prefetch_create(n_slots=2) -> int:
+    """wk_prefetch_create -> opaque handle (an integer address)."""
+    h = C.c_void_p()
+    _check(lib().wk_prefetch_create(C.byref(h), n_slots), "wk_prefetch_create")
+    return h.value
+
+
+def wk_prefetch_destroy(p):
+    _check(lib().wk_prefetch_destroy(p), "wk_prefetch_destroy")
+
+
+def wk_prefetch_stream(p) -> int:
+    """The copy stream as a raw hipStream_t; wrap with torch.cuda.ExternalStream to enqueue torch work."""
+    return lib().wk_prefetch_stream(p)
+
+
+def wk_prefetch_after(p, stream=None):
+    _check(lib().wk_prefetch_after(p, _stream() if stream is None else stream), "wk_prefetch_after")
+
+
+def wk_prefetch_gather(p, slot, store_desc: wk_store_desc, ids, n_ids, R_max, K_native, V_native, n_native, K_win,
+                       V_win, win_capacity, n_win, max_workgroups=0):
+    st = lib().wk_prefetch_gather(p, slot, C.byref(store_desc), _dev(ids, "ids", torch.int32),
+                                  _dev(n_ids, "n_ids", torch.int32), R_max, _dev(K_native, "K_native"),
+                                  _dev(V_native, "V_native"), n_native, _dev(K_win, "K_win"), _dev(V_win, "V_win"),
+                                  win_capacity, _dev(n_win, "n_win", torch.int32), max_workgroups)
+    _check(st, "wk_prefetch_gather")
+
+
+def wk_prefetch_acquire(p, slot, stream=None):
+    _check(lib().wk_prefetch_acquire(p, slot, _stream() if stream is None else stream), "wk_prefetch_acquire")
+
+
+def wk_prefetch_release(p, slot, stream=None):
+    _check(lib().wk_prefetch_release(p, slot, _stream() if stream is None else stream), "wk_prefetch_release")
 
 
 def wk_attention_workspace_bytes(H, N_q, N_kv, dtype) -> int:

@@ -19,6 +19,11 @@ __host__ __device__ inline size_t esize(int dtype) { return dtype == WK_BF16 ? 2
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// wk_gather_window with a cap on the number of workgroups (0 = one per 32 KB work unit)
+wk_status gather_launch(const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids, int32_t R_max,
+                        const void *K_native, const void *V_native, int32_t n_native, void *K_win, void *V_win,
+                        int32_t win_capacity, int32_t *n_win, int32_t max_workgroups, hipStream_t stream);
+
 // 16 lanes share one 128-element row; each lane owns elements 8*sub .. 8*sub+7.
 constexpr int kRowLanes = 16;
 

@@ -139,6 +139,17 @@ def test_argument_validation_of_the_other_calls():
     assert L.wk_chunk_lse(C.byref(sd64), one, 8, 0.0, one, None) == wk.WK_ERR_UNSUPPORTED
     sd0 = wk.wk_store_desc(None, None, None, 0, 0, 2, 128, wk.WK_BF16)
     assert L.wk_chunk_lse(C.byref(sd0), one, 8, 0.0, one, None) == wk.WK_OK      # empty store: nothing to do
+    # prefetch handle: argument checks that need no device
+    h = C.c_void_p()
+    assert L.wk_prefetch_create(None, 2) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_prefetch_create(C.byref(h), 0) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_prefetch_create(C.byref(h), 9) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_prefetch_destroy(None) == wk.WK_OK
+    assert L.wk_prefetch_stream(None) is None
+    assert L.wk_prefetch_after(None, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_prefetch_acquire(None, 0, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_prefetch_release(None, 0, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_prefetch_gather(None, 0, C.byref(sd), one, None, 2, one, one, 5, one, one, 64, None, 0) == wk.WK_ERR_INVALID_ARG
     # key-range splits are only proposed when the plain grid would leave compute units idle
     assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
     assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4
