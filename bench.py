@@ -241,6 +241,33 @@ def main():
         extra["ms_per_chunk"]["gather_pinned_host"] = t_pin
         extra["gather_pinned_host_GBps"] = link_bytes / (t_pin * 1e-3) / 1e9
         extra["ms_per_step_pinned_store"] = ms_step - per_call["gather_hbm"] + t_pin
+        # in-place refresh of the retrieved slots (Sec. 4.2 window regions): only chunks that are not resident
+        # yet cross the host link.  Two id sets differing in k chunks are requested in turn.
+        slot_ids = torch.full((cfg.R,), -1, dtype=torch.int32, device=dev)
+        n_fetched = torch.zeros(1, dtype=torch.int32, device=dev)
+        u_ws = torch.empty(wk.wk_window_update_workspace_bytes(cfg.R), dtype=torch.uint8, device=dev)
+        base_ids = ids.clone()
+        refresh = {}
+        for k in (0, 1, 2, cfg.R):
+            other = base_ids.clone()
+            spare = [c for c in range(cfg.M) if c not in set(base_ids.tolist())][:k]
+            other[:k] = torch.tensor(spare, dtype=torch.int32, device=dev)
+            sets = [base_ids, other]
+            wk.wk_window_update(pstore.desc, base_ids, n_found, cfg.R, n_out, slot_ids, cfg.n_native, Kw, Vw, N_kv,
+                                n_win, n_fetched, u_ws)
+            torch.cuda.synchronize()
+            ts = []
+            for rep in range(4):
+                s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                s_ev.record()
+                wk.wk_window_update(pstore.desc, sets[(rep + 1) % 2], n_found, cfg.R, n_out, slot_ids, cfg.n_native,
+                                    Kw, Vw, N_kv, n_win, n_fetched, u_ws)
+                e_ev.record()
+                torch.cuda.synchronize()
+                assert int(n_fetched.item()) == k
+                ts.append(s_ev.elapsed_time(e_ev))
+            refresh[f"{k}_of_{cfg.R}_chunks_change"] = float(np.median(ts))
+        extra["window_update_pinned_host_ms"] = refresh
         # offload overlap (Sec. 7): a loop over layers (each a gather from the pinned store + attention),
         # on one stream vs with the next layer's gather on the prefetch stream into a second window buffer
         n_layers, cap_wg = 6, 64

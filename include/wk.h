@@ -238,6 +238,66 @@ size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_
 wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int32_t N_q, float scale,
                        float *lse_out, void *hip_stream);
 
+/* ---- Window bookkeeping (Sec. 4.2: sink, retrieved, recent and denoising regions of the sliding
+ * window; Sec. 5.1: 3 + 9 + 3 + 3 latent frames).  Physical rows of a window buffer, per head:
+ *
+ *     [ sink_chunks chunks | ring of recent_chunks + 1 chunk slots | R retrieved slots ]
+ *
+ * each chunk chunk_frames * T rows, each retrieved slot slot_tokens rows.  The chunk being generated
+ * and the recent chunks rotate over the ring slots (no copy when a chunk turns from "denoising"
+ * into "recent"); the order of regions is free because attention sums over all window keys. */
+typedef struct wk_window_desc {
+    int32_t T;             /* tokens per latent frame */
+    int32_t chunk_frames;  /* latent frames per generated chunk (3) */
+    int32_t sink_chunks;   /* initial chunks kept for ever (1 = 3 sink frames) */
+    int32_t recent_chunks; /* chunks kept behind the one being generated (1 = 3 recent frames) */
+    int32_t R;             /* retrieved slots (6 compressed chunks = 9 frames at 3 -> 1.5) */
+    int32_t slot_tokens;   /* rows per retrieved slot = stored tokens of a compressed chunk */
+} wk_window_desc;
+
+typedef struct wk_window_step {
+    int32_t denoise_row0;   /* the K/V of the chunk being generated live at rows [denoise_row0, +denoise_rows) */
+    int32_t denoise_rows;
+    int32_t n_native;       /* rows [0, n_native) are the valid sink + recent + denoising rows at this step */
+    int32_t evict;          /* 1: rows [evict_row0, +denoise_rows) still hold chunk evict_chunk, which must be
+                               compressed into the store as chunk store_id BEFORE the new chunk's K/V are
+                               written there (same rows) */
+    int32_t evict_row0;
+    int32_t store_id;       /* -1 when evict == 0 */
+    int64_t evict_chunk;    /* generation index of the chunk leaving the window; -1 when evict == 0 */
+    int32_t M;              /* stored chunks available to retrieval at this step (eviction included) */
+    int32_t retrieved_row0; /* first row of the retrieved slots (= n_native once the ring is full) */
+    int32_t win_capacity;   /* rows per head of the window buffer */
+} wk_window_step;
+
+/* Host arithmetic: the placement for generated chunk chunk_index (0, 1, 2, ...).
+ * Errors: INVALID_ARG, UNSUPPORTED (a count does not fit in 31 bits). */
+wk_status wk_window_plan(const wk_window_desc *w, int64_t chunk_index, wk_window_step *out);
+
+/* In-place refresh of the retrieved region (Sec. 4.2: the top-k chunks "fill this region").  slot_ids
+ * says which stored chunk each of the R slots holds (-1: none); ids are the chunks wanted now (from
+ * wk_score_chunks or wk_score_chunks_query).  Ids that are out of range, repeat an earlier one, or
+ * name a chunk whose n_tok differs from slot_tokens are dropped; n are left.  Afterwards exactly slots
+ * 0..n-1 are in use: a wanted chunk that is already resident keeps its slot and is not copied; the
+ * others are copied from the store (HBM or pinned host) into the remaining slots below n, ascending,
+ * in the order of ids.  If a resident wanted chunk sits at or beyond slot n the region is rebuilt
+ * (slot j = j-th wanted chunk), copying only slots whose content changes.
+ *
+ *   ids, n_ids device, as for wk_gather_window (NULL n_ids = R)
+ *   slot_ids   device in/out, [R] int32
+ *   n_native   first row of slot 0 (wk_window_step.retrieved_row0)
+ *   n_win      device out, int32 = n_native + n * slot_tokens.  May be NULL.
+ *   n_fetched  device out, int32 = chunks copied by this call.  May be NULL.
+ *   workspace  device, wk_window_update_workspace_bytes(R) bytes, 256-byte aligned
+ *   max_workgroups  > 0 caps the copy grid (see wk_prefetch_gather); 0 = one per 32 KB
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, R > 1024), SHAPE (slots exceed win_capacity), WORKSPACE. */
+wk_status wk_window_update(const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids, int32_t R,
+                           int32_t slot_tokens, int32_t *slot_ids, int32_t n_native, void *K_win,
+                           void *V_win, int32_t win_capacity, int32_t *n_win, int32_t *n_fetched,
+                           void *workspace, size_t workspace_bytes, int32_t max_workgroups,
+                           void *hip_stream);
+size_t wk_window_update_workspace_bytes(int32_t R);
+
 /* ---- Overlap of a CPU-offloaded store with attention (Sec. 7: the host-to-device transfer at
  * retrieval time is the stated obstacle to real time with all KV chunks in CPU memory).
  *

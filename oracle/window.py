@@ -46,7 +46,8 @@ def update_slots(slot_ids, ids, R, valid):
     slot_ids: chunk id per slot before the call (-1 = empty); ids: the chunks wanted now, in
     rank order; valid(id) says whether an id may be placed.  Wanted ids that are invalid or repeat an
     earlier one are dropped; n = number left.  Afterwards exactly slots 0..n-1 are used.  A chunk that
-    is wanted and already sits in a slot stays where it is; the wanted chunks not yet resident take
+    is wanted and already sits in a slot stays where it is (the first such slot, should a corrupt
+    table name it twice); the wanted chunks not yet resident take
     the remaining slots below n in ascending slot order, in rank order.  If a resident wanted chunk
     sits in a slot >= n the region is rebuilt (slot j <- j-th wanted chunk).
     Returns (new_slot_ids, fetched) with fetched = [(slot, id), ...] in slot order."""
@@ -56,7 +57,8 @@ def update_slots(slot_ids, ids, R, valid):
             want.append(i)
     want = want[:R]
     n = len(want)
-    kept = {s: slot_ids[s] for s in range(R) if slot_ids[s] >= 0 and slot_ids[s] in want}
+    kept = {s: slot_ids[s] for s in range(R)
+            if slot_ids[s] >= 0 and slot_ids[s] in want and slot_ids[s] not in slot_ids[:s]}
     new = [-1] * R
     if any(s >= n for s in kept):
         for j, i in enumerate(want):

@@ -27,6 +27,7 @@ WK_QUERY_MAX_CHUNKS = 1024
 EXPORTS = [
     "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
     "wk_score_chunks_query", "wk_score_chunks_query_workspace_bytes", "wk_chunk_lse",
+    "wk_window_plan", "wk_window_update", "wk_window_update_workspace_bytes",
     "wk_prefetch_create", "wk_prefetch_destroy", "wk_prefetch_stream", "wk_prefetch_after", "wk_prefetch_gather",
     "wk_prefetch_acquire", "wk_prefetch_release",
     "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_attention_workspace_bytes",
@@ -51,6 +52,17 @@ class wk_store_desc(C.Structure):
     _fields_ = [("K_ptr", C.c_void_p), ("V_ptr", C.c_void_p), ("n_tok", C.c_void_p),
                 ("M", C.c_int32), ("max_tok", C.c_int32), ("H", C.c_int32), ("d", C.c_int32),
                 ("dtype", C.c_int32)]
+
+
+class wk_window_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("T", "chunk_frames", "sink_chunks", "recent_chunks", "R", "slot_tokens")]
+
+
+class wk_window_step(C.Structure):
+    _fields_ = [("denoise_row0", C.c_int32), ("denoise_rows", C.c_int32), ("n_native", C.c_int32),
+                ("evict", C.c_int32), ("evict_row0", C.c_int32), ("store_id", C.c_int32),
+                ("evict_chunk", C.c_int64), ("M", C.c_int32), ("retrieved_row0", C.c_int32),
+                ("win_capacity", C.c_int32)]
 
 
 _lib = None
@@ -85,6 +97,13 @@ def lib():
         L.wk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, vp, C.c_size_t, vp]
         L.wk_chunk_lse.restype = C.c_int
         L.wk_chunk_lse.argtypes = [C.POINTER(wk_store_desc), vp, i32, f32, vp, vp]
+        L.wk_window_plan.restype = C.c_int
+        L.wk_window_plan.argtypes = [C.POINTER(wk_window_desc), C.c_int64, C.POINTER(wk_window_step)]
+        L.wk_window_update.restype = C.c_int
+        L.wk_window_update.argtypes = [C.POINTER(wk_store_desc), vp, vp, i32, i32, vp, i32, vp, vp, i32, vp, vp, vp,
+                                       C.c_size_t, i32, vp]
+        L.wk_window_update_workspace_bytes.restype = C.c_size_t
+        L.wk_window_update_workspace_bytes.argtypes = [i32]
         L.wk_prefetch_create.restype = C.c_int
         L.wk_prefetch_create.argtypes = [C.POINTER(vp), i32]
         L.wk_prefetch_destroy.restype = C.c_int
@@ -253,6 +272,30 @@ def wk_chunk_lse(store_desc: wk_store_desc, Q, lse_out, scale=0.0):
                             _dev(lse_out, "lse_out", torch.float32), _stream())
     _check(st, "wk_chunk_lse")
     return lse_out
+
+
+def wk_window_plan(desc: wk_window_desc, chunk_index: int) -> wk_window_step:
+    """wk_window_plan (host)."""
+    out = wk_window_step()
+    _check(lib().wk_window_plan(C.byref(desc), chunk_index, C.byref(out)), "wk_window_plan")
+    return out
+
+
+def wk_window_update_workspace_bytes(R) -> int:
+    return lib().wk_window_update_workspace_bytes(R)
+
+
+def wk_window_update(store_desc: wk_store_desc, ids, n_ids, R, slot_tokens, slot_ids, n_native, K_win, V_win,
+                     win_capacity, n_win, n_fetched, workspace, max_workgroups=0):
+    """wk_window_update."""
+    st = lib().wk_window_update(C.byref(store_desc), _dev(ids, "ids", torch.int32), _dev(n_ids, "n_ids", torch.int32),
+                                R, slot_tokens, _dev(slot_ids, "slot_ids", torch.int32), n_native,
+                                _dev(K_win, "K_win"), _dev(V_win, "V_win"), win_capacity,
+                                _dev(n_win, "n_win", torch.int32), _dev(n_fetched, "n_fetched", torch.int32),
+                                _dev(workspace, "workspace"),
+                                0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                max_workgroups, _stream())
+    _check(st, "wk_window_update")
 
 
 def wk_prefetch_create(n_slots=2) -> int:

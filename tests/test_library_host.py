@@ -165,3 +165,64 @@ def test_argument_validation_of_the_other_calls():
     sd64 = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 64, wk.WK_BF16)
     assert L.wk_gather_window(C.byref(sd64), one, None, 2, one, one, 5, one, one, 25, None, None) == wk.WK_ERR_UNSUPPORTED
     assert L.wk_host_device_pointer(None, None) == wk.WK_ERR_INVALID_ARG
+
+
+def test_window_plan_matches_the_rolling_window_simulation():
+    """The planner's row arithmetic, applied to a label array standing for the window rows, must put
+    every generated chunk exactly where the oracle's simulation says it lives (Sec. 4.2 regions)."""
+    from oracle.window import RollingWindow
+    for sink_chunks, recent_chunks, frames, T in [(1, 1, 3, 5), (1, 2, 3, 4), (2, 1, 2, 3), (0, 1, 3, 2), (1, 0, 1, 7)]:
+        desc = wk.wk_window_desc(T, frames, sink_chunks, recent_chunks, 6, 11)
+        sim = RollingWindow(sink_chunks, recent_chunks)
+        rows = None
+        stored = []
+        for c in range(30):
+            p = wk.wk_window_plan(desc, c)
+            region, slot, evicted = sim.step(c)
+            chunk_rows = frames * T
+            if rows is None:
+                rows = np.full(p.win_capacity, -1, np.int64)
+                assert p.win_capacity == (sink_chunks + recent_chunks + 1) * chunk_rows + 6 * 11
+                assert p.retrieved_row0 == (sink_chunks + recent_chunks + 1) * chunk_rows
+            assert p.denoise_rows == chunk_rows
+            if p.evict:
+                assert evicted is not None and p.evict_chunk == evicted
+                assert np.all(rows[p.evict_row0:p.evict_row0 + chunk_rows] == evicted)   # it is still there
+                assert p.store_id == len(stored)
+                stored.append(evicted)
+            else:
+                assert evicted is None and p.store_id == -1 and p.evict_chunk == -1
+                assert np.all(rows[p.denoise_row0:p.denoise_row0 + chunk_rows] == -1)    # never overwrite unsaved rows
+            rows[p.denoise_row0:p.denoise_row0 + chunk_rows] = c
+            assert stored == sim.store and p.M == len(sim.store)
+            # the valid native rows are a prefix and hold exactly sink + ring
+            live = sorted(set(rows[:p.n_native].tolist()))
+            assert live == sorted(list(sim.sink) + list(sim.ring))
+            assert np.all(rows[p.n_native:p.retrieved_row0] == -1)
+            if p.M > 0:
+                assert p.n_native == p.retrieved_row0        # retrieval starts only once the ring is full
+    # paper shape: 18 frames of 880 tokens with 6 slots of 1.5 frames
+    desc = wk.wk_window_desc(880, 3, 1, 1, 6, 1320)
+    p = wk.wk_window_plan(desc, 10)
+    assert p.win_capacity == 18 * 880 and p.n_native == 9 * 880 and p.M == 8
+    L = wk.lib()
+    assert L.wk_window_plan(None, 0, C.byref(p)) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_window_plan(C.byref(desc), -1, C.byref(p)) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_window_plan(C.byref(wk.wk_window_desc(0, 3, 1, 1, 6, 10)), 0, C.byref(p)) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_window_plan(C.byref(wk.wk_window_desc(1 << 20, 1 << 10, 1, 1, 6, 10)), 0, C.byref(p)) == wk.WK_ERR_UNSUPPORTED
+    # wk_window_update argument checks
+    one = C.c_void_p(256)
+    sd = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 128, wk.WK_BF16)
+    def upd(**kw):
+        a = dict(dict(R=2, slot=10, slots=one, n_native=5, cap=64, ws=one, ws_bytes=1 << 16, ids=one), **kw)
+        return L.wk_window_update(C.byref(sd), a["ids"], None, a["R"], a["slot"], a["slots"], a["n_native"], one, one,
+                                  a["cap"], None, None, a["ws"], a["ws_bytes"], 0, None)
+    assert upd(R=-1) == wk.WK_ERR_INVALID_ARG
+    assert upd(slot=0) == wk.WK_ERR_INVALID_ARG
+    assert upd(slots=None) == wk.WK_ERR_INVALID_ARG
+    assert upd(ids=None) == wk.WK_ERR_INVALID_ARG
+    assert upd(R=1025) == wk.WK_ERR_UNSUPPORTED
+    assert upd(cap=24) == wk.WK_ERR_SHAPE
+    assert upd(ws=None) == wk.WK_ERR_WORKSPACE
+    assert upd(ws_bytes=8) == wk.WK_ERR_WORKSPACE
+    assert wk.wk_window_update_workspace_bytes(1025) == 0 and wk.wk_window_update_workspace_bytes(6) >= 256 + 48
