@@ -24,7 +24,7 @@ import wk_synth as ws
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM bytes per wk_attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs),
 # per workload index; see profiles/hbm_traffic_lingbot_pmc.txt for the commands and the calibration
-MEASURED_ATTENTION_TRAFFIC = {2: (425051 + 63520) * 1024}
+MEASURED_ATTENTION_TRAFFIC = {2: (418970 + 51360) * 1024}
 
 
 def parse():

@@ -54,16 +54,26 @@ constexpr int kXcds = 8;
 // [x*per_xcd, (x+1)*per_xcd) keeps the query tiles that stream the same head's K/V on one XCD,
 // so that head's window is fetched from HBM once into that XCD's L2 instead of once per tile.
 // With a split key range the items of one head are ordered split-major, so the query tiles that
-// stream the same slice of K/V stay neighbours.  A batch over stored chunks is chunk-major.
+// stream the same slice of K/V stay neighbours.  A batch over stored chunks (one key range each)
+// is ordered head, chunk, query tile: a head's queries stay in the XCD's L2 while the chunks' keys
+// stream through once.
 __device__ inline bool work_item(const AttnArgs &a, int &c, int &h, int &qt, int &sp) {
     const int lin = blockIdx.x;
-    const int per_chunk = a.H * a.n_qtiles * a.splits;
     const int w = (lin % kXcds) * a.per_xcd + lin / kXcds;
-    if (lin / kXcds >= a.per_xcd || w >= per_chunk * (a.n_chunks > 0 ? a.n_chunks : 1)) return false;
-    c = w / per_chunk;
-    const int wc = w % per_chunk;
-    h = wc / (a.n_qtiles * a.splits);
-    const int rem = wc % (a.n_qtiles * a.splits);
+    if (lin / kXcds >= a.per_xcd) return false;
+    if (a.n_chunks > 0) {
+        const int per_head = a.n_chunks * a.n_qtiles;
+        if (w >= a.H * per_head) return false;
+        h = w / per_head;
+        c = (w % per_head) / a.n_qtiles;
+        qt = w % a.n_qtiles;
+        sp = 0;
+        return true;
+    }
+    if (w >= a.H * a.n_qtiles * a.splits) return false;
+    c = 0;
+    h = w / (a.n_qtiles * a.splits);
+    const int rem = w % (a.n_qtiles * a.splits);
     sp = rem / a.n_qtiles;
     qt = rem % a.n_qtiles;
     return true;
@@ -253,13 +263,9 @@ __device__ inline float max_across_halves(float x) {
 #define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
-// WITH_O = false: only the log-sum-exp is wanted (a.O is NULL, one key range).  The V tiles are
-// neither loaded nor multiplied; the row sums are formed exactly as in the full kernel.
-template <int WAVES, bool WITH_O>
+template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
-    // s_waitcnt that lets one tile's loads of this wave (4 with V, 2 without) stay in flight
-    constexpr int kWaitOneTile = WITH_O ? 0x0F74 : 0x0F72;
     extern __shared__ __attribute__((aligned(256))) char smem[];
     int c, h, qt, sp;
     if (!work_item(a, c, h, qt, sp)) return;
@@ -282,10 +288,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     if (t0 >= t1) {   // empty window, or a split past its end: contributes nothing
         if (q_ok) {
             if (a.splits == 1) {
-                if constexpr (WITH_O) {
-                    char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
-                    for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
-                }
+                char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+                for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
                 if (lse && g == 0) lse[(size_t)h * a.N_q + q] = -INFINITY;
             } else {
                 const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
@@ -346,8 +350,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + (t_off + k_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
-                if constexpr (WITH_O)
-                    __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
             }
         } else {
 #pragma unroll
@@ -355,8 +358,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                 const unsigned ko = min(t_off + k_src[i], last_off + (k_src[i] & 255u));
                 const unsigned vo = min(t_off + v_src[i], last_off + (v_src[i] & 255u));
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + ko), WK_LDS(dst + i * 1024), 16, 0, 0);
-                if constexpr (WITH_O)
-                    __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
             }
         }
     };
@@ -402,12 +404,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             l_run *= alpha;
-            if constexpr (WITH_O) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
-            }
+                for (int r = 0; r < 16; ++r) o[b][r] *= alpha;
         }
     };
     // p = exp2(s*c - m) rounded to bf16; registers 8*t2 .. 8*t2+7 of block b -> k step 2*b + t2.
@@ -430,7 +430,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                 }
     };
     auto accumulate_pv = [&](int byte_off, const bf16x8 (&pb)[4]) {
-        if constexpr (!WITH_O) return;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
@@ -450,7 +449,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     issue_tile(t0, sh);
     issue_tile(t0 + 1, (sh + 1) & 3);
     issue_tile(t0 + 2, (sh + 2) & 3);
-    __builtin_amdgcn_s_waitcnt(kWaitOneTile);   // tiles 0 and 1 of this wave have landed
+    __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tiles 0 and 1 of this wave have landed
     __syncthreads();
     f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
     float mt;
@@ -467,7 +466,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
         probabilities(s_cur, pb);
         accumulate_pv(POS * kTileBytes, pb);
         mt = tile_max(s_next);
-        __builtin_amdgcn_s_waitcnt(kWaitOneTile);   // everything but tile j+3 has landed
+        __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): everything but tile j+3 has landed
         __syncthreads();
     };
     using P0 = std::integral_constant<int, 0>;
@@ -509,24 +508,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (q_ok && a.splits == 1) {
-        if constexpr (WITH_O) {
-            char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
-            const float inv = 1.f / l_tot;
+        char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+        const float inv = 1.f / l_tot;
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int dv = 32 * b + 8 * t + 4 * g;
-                    const bf16x2 lo = __builtin_convertvector(f32x2{o[b][4 * t] * inv, o[b][4 * t + 1] * inv}, bf16x2);
-                    const bf16x2 hi = __builtin_convertvector(f32x2{o[b][4 * t + 2] * inv, o[b][4 * t + 3] * inv}, bf16x2);
-                    uint2 w;
-                    w.x = __builtin_bit_cast(uint32_t, lo);
-                    w.y = __builtin_bit_cast(uint32_t, hi);
-                    *reinterpret_cast<uint2 *>(Orow + dv * 2) = w;
-                }
-        }
+            for (int t = 0; t < 4; ++t) {
+                const int dv = 32 * b + 8 * t + 4 * g;
+                const bf16x2 lo = __builtin_convertvector(f32x2{o[b][4 * t] * inv, o[b][4 * t + 1] * inv}, bf16x2);
+                const bf16x2 hi = __builtin_convertvector(f32x2{o[b][4 * t + 2] * inv, o[b][4 * t + 3] * inv}, bf16x2);
+                uint2 w;
+                w.x = __builtin_bit_cast(uint32_t, lo);
+                w.y = __builtin_bit_cast(uint32_t, hi);
+                *reinterpret_cast<uint2 *>(Orow + dv * 2) = w;
+            }
         if (lse && g == 0) lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
-    } else if (WITH_O && q_ok) {   // partial result of this key range, merged by k_attn_merge
+    } else if (q_ok) {   // partial result of this key range, merged by k_attn_merge
         const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
         float *Po = a.part_o + row * WK_D;
 #pragma unroll
@@ -537,6 +534,153 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                     float4{o[b][4 * t], o[b][4 * t + 1], o[b][4 * t + 2], o[b][4 * t + 3]};
         if (g == 0) { a.part_ml[row * 2] = m_run; a.part_ml[row * 2 + 1] = l_tot; }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Log-sum-exp only (a.O == NULL; query-based retrieval, paper Sec. 4.2 / App. C).  Without the
+// P V product the matrix work halves while the exp2 work per key stays, so the kernel is bound
+// by the VALU, not by the matrix cores.  It therefore drops the in-wave software pipeline of
+// k_attn_bf16 (two S^T tiles in registers) for occupancy: under 128 VGPRs and with a 64 KB K
+// ring, two workgroups = four waves per SIMD share a CU, and one wave's MFMAs run under the
+// others' exp2.  Same tile layout, loads and arithmetic (bf16-rounded probabilities summed by
+// dot2) as the full kernel: the lse values are bit-identical to those wk_attention returns
+// beside O.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512, 4) void k_lse_bf16(AttnArgs a) {
+    extern __shared__ __attribute__((aligned(256))) char smem[];
+    int c, h, qt, sp;
+    if (!work_item(a, c, h, qt, sp)) return;
+    const Window win = window_of(a, c);
+    const int n_kv = win.n_kv;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, g = lane >> 5;
+    const int q = qt * 256 + wave * 32 + col;
+    const bool q_ok = q < a.N_q;
+    const int q_ld = q_ok ? q : a.N_q - 1;
+    const char *Qrow = a.Q + ((size_t)h * a.N_q + q_ld) * 256;
+    float *const out = win.lse + (size_t)h * a.N_q + q;
+    if (n_kv == 0) {
+        if (q_ok && g == 0) *out = -INFINITY;
+        return;
+    }
+    bf16x8 qb[8];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) qb[st] = *reinterpret_cast<const bf16x8 *>(Qrow + (2 * st + g) * 16);
+    const char *k_rd[8];   // as in k_attn_bf16: chunk 2*st + g of key col, slot c ^ (key & 15)
+#pragma unroll
+    for (int st = 0; st < 8; ++st) k_rd[st] = smem + col * 256 + (((2 * st + g) ^ (col & 15)) << 4);
+    unsigned k_src[2];
+    {
+        const int r = lane >> 4, p = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int R = 4 * (2 * wave + i) + r;
+            k_src[i] = R * 256 + ((p ^ (R & 15)) << 4);
+        }
+    }
+    const char *Kh = win.K + (size_t)h * win.stride * 256;
+    const unsigned last_off = (unsigned)(n_kv - 1) * 256u;
+    char *const dma_dst = smem + wave * 2048;
+    // 2 loads per wave and tile; tiles that end past the window (also the look-ahead past the last
+    // tile) clamp their rows to the last key
+    auto issue_tile = [&](int t, int slot) {
+        const unsigned t_off = (unsigned)t * (kKeys * 256u);
+        char *dst = dma_dst + slot * kTileBytes;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const unsigned ko = min(t_off + k_src[i], last_off + (k_src[i] & 255u));
+            __builtin_amdgcn_global_load_lds(WK_GLB(Kh + ko), WK_LDS(dst + i * 1024), 16, 0, 0);
+        }
+    };
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c_log2 = a.scale_log2;
+    auto tile = [&](int byte_off, int kt, bool partial) {
+        f32x16 s[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
+#pragma unroll
+        for (int st = 0; st < 8; ++st)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(k_rd[st] + byte_off + b * 8192);
+                s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[st], s[b], 0, 0, 0);
+            }
+        if (partial) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kt + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (key >= n_kv) s[b][r] = -INFINITY;
+                }
+        }
+        float mx[10];
+#pragma unroll
+        for (int i = 0; i < 10; ++i) {
+            const int e = 3 * i;
+            mx[i] = max3(s[e >> 4][e & 15], s[(e + 1) >> 4][(e + 1) & 15], s[(e + 2) >> 4][(e + 2) & 15]);
+        }
+        float m = max3(max3(mx[0], mx[1], mx[2]), max3(mx[3], mx[4], mx[5]), max3(mx[6], mx[7], mx[8]));
+        m = max3(m, mx[9], fmaxf(s[1][14], s[1][15]));
+        const float mt = max_across_halves(m) * c_log2;
+        if (__any(mt > m_run + 8.0f)) {   // lazy rescale, as in k_attn_bf16
+            const float m_new = fmaxf(m_run, mt);
+            l_run *= __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+        }
+        const float neg_m = -m_run;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[b][e], c_log2, neg_m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c_log2, neg_m));
+                l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_convertvector(f32x2{p0, p1}, bf16x2), ones, l_run,
+                                                        false);
+            }
+    };
+    const int n_full = n_kv / kKeys;   // full tiles; one partial tile may follow
+    issue_tile(0, 0);
+    issue_tile(1, 1);
+    issue_tile(2, 2);
+    // step j: tile j of every wave has landed (vmcnt(4) leaves tiles j+1, j+2 in flight) and every
+    // wave is done with tile j-1, whose slot tile j+3 may now overwrite
+    auto step = [&](int j, auto pos_tag, bool partial) {
+        constexpr int POS = decltype(pos_tag)::value;
+        __builtin_amdgcn_s_waitcnt(0x0F74);
+        __syncthreads();
+        issue_tile(j + 3, (POS + 3) & 3);
+        tile(POS * kTileBytes, j * kKeys, partial);
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
+    int j = 0;
+    for (; j + 4 <= n_full; j += 4) {
+        step(j, P0{}, false);
+        step(j + 1, P1{}, false);
+        step(j + 2, P2{}, false);
+        step(j + 3, P3{}, false);
+    }
+    const int rest = n_full - j;   // 0..3 full tiles, then perhaps the partial one, at positions 0, 1, ...
+    const bool tail = n_full * kKeys < n_kv;
+    if (rest > 0) step(j, P0{}, false);
+    if (rest > 1) step(j + 1, P1{}, false);
+    if (rest > 2) step(j + 2, P2{}, false);
+    if (tail) {
+        if (rest == 0) step(j, P0{}, true);
+        else if (rest == 1) step(j + 1, P1{}, true);
+        else if (rest == 2) step(j + 2, P2{}, true);
+        else step(j + 3, P3{}, true);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped look-ahead loads before the LDS is released
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (q_ok && g == 0) *out = (m_run + log2f(l_tot)) * 0.6931471805599453f;
 }
 
 // Merge of the key-range splits: O = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, m = max_s m_s.
@@ -603,17 +747,15 @@ wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipSt
     a.per_xcd = (items + kXcds - 1) / kXcds;
     static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
     if (!lds_limit_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES, false>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
             return WK_ERR_HIP;
         lds_limit_set = true;
     }
     if (a.O)
-        hipLaunchKernelGGL((k_attn_bf16<WAVES, true>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
+        hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
     else
-        hipLaunchKernelGGL((k_attn_bf16<WAVES, false>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
+        hipLaunchKernelGGL(k_lse_bf16, dim3(a.per_xcd * kXcds), dim3(512), kVRing, st, a);
     WK_LAUNCH_CHECK();
     if (a.splits > 1) {
         const size_t rows = (size_t)a.H * a.N_q;

@@ -203,12 +203,17 @@ __global__ __launch_bounds__(kThreads) void k_query_topk(const double *__restric
         if (mass_out) mass_out[r] = -INFINITY;
     }
     if (M == 0) return;
-    for (int c = tid; c < M; c += kThreads) {
+    // one wave per chunk: lanes sum interleaved blocks, then a fixed-shape tree over the lanes
+    for (int c = tid >> 6; c < M; c += kThreads / 64) {
         double s = 0.0;
-        for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * M + c];
+        for (int b = tid & 63; b < n_blocks; b += 64) s += partial[(size_t)b * M + c];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
         s /= (double)n_rows;
-        mass[c] = s;
-        mass_all[c] = s;
+        if ((tid & 63) == 0) {
+            mass[c] = s;
+            mass_all[c] = s;
+        }
     }
     __syncthreads();
     for (int c = tid; c < M; c += kThreads) {
