@@ -181,6 +181,29 @@ def attention(Q, K, V, N_kv=None, scale=None, rows=None, want_lse=False):
     return (O, lse) if want_lse else O
 
 
+def attention_block_causal(Q, K, V, denoise_row0, frame_T, N_kv=None, scale=None, rows=None, want_lse=False):
+    """fp64 attention with the frame-level causal mask inside the denoising chunk, whose keys are window
+    rows [denoise_row0, denoise_row0 + N_q)."""
+    _chk(Q), _chk(K), _chk(V)
+    H, N_q, d = Q.shape
+    stride = K.shape[1]
+    N_kv = stride if N_kv is None else N_kv
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, np.int32)
+        n_rows = rows.size
+    else:
+        n_rows = N_q
+    O = np.zeros((H, n_rows, d), np.float64)
+    lse = np.zeros((H, n_rows), np.float64)
+    rc = lib().wko_attention_block_causal(_p(Q), _p(K), _p(V), _code(Q), H, C.c_int64(N_q), C.c_int64(N_kv), d,
+                                          C.c_int64(stride), C.c_double(scale), C.c_int64(denoise_row0),
+                                          C.c_int64(frame_T), _p(rows), C.c_int64(n_rows), _p(O), _p(lse))
+    if rc != 0:
+        raise ValueError(f"attention_block_causal failed ({rc})")
+    return (O, lse) if want_lse else O
+
+
 def score_chunks_query(Q, K_chunks, R, scale=None):
     """Query-based retrieval: ids [min(R,M)], mass_sel, mass_all [M] (attention mass per stored chunk)."""
     _chk(Q)

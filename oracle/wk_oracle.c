@@ -30,6 +30,11 @@
  *        Sec. 4.2).
  *   wko_attention
  *        softmax attention over the assembled window (Sec. 4.2, Sec. 4.3).
+ *   wko_attention_block_causal
+ *        the same with a frame-level causal mask inside the chunk being denoised: an option
+ *        (the paper states no mask; frame-causal attention inside a chunk is a property some
+ *        autoregressive video backbones of Sec. 3 have).  Parity unpinned against any model;
+ *        pinned against a library masked softmax and against wko_attention on reduced windows.
  *
  * Readings of silent points (each repeated where it is used):
  *   - zero-norm key: its cosine terms are 0;
@@ -521,6 +526,67 @@ int wko_attention(const void *Q, const void *K, const void *V, int dtype, int H,
                     double *o = O + ((size_t)h * n_rows + r) * d;
                     for (int c = 0; c < d; ++c) o[c] = 0.0;
                     for (int64_t n = 0; n < N_kv; ++n) {
+                        size_t base = ((size_t)h * kv_row_stride + n) * d;
+                        double p = z[n] / denom;
+                        for (int c = 0; c < d; ++c) o[c] += p * load_elem(V, dtype, base + c);
+                    }
+                    if (lse) lse[(size_t)h * n_rows + r] = zmax + log(denom);
+                }
+        }
+        free(z); free(q);
+    }
+    return fail ? -2 : 0;
+}
+
+/* Attention with a frame-level causal mask inside the chunk being denoised.  The N_q queries are
+ * the chunk's tokens, N_q / frame_T frames of frame_T tokens; their own keys occupy window rows
+ * [denoise_row0, denoise_row0 + N_q) in the same order.  Query i sees every window row outside
+ * that range, and inside it the rows of frames 0 .. i / frame_T (its own frame included).
+ * Everything else as wko_attention. */
+int wko_attention_block_causal(const void *Q, const void *K, const void *V, int dtype, int H, int64_t N_q,
+                               int64_t N_kv, int d, int64_t kv_row_stride, double scale, int64_t denoise_row0,
+                               int64_t frame_T, const int32_t *rows, int64_t n_rows, double *O, double *lse)
+{
+    if (!Q || !K || !V || !O || H < 1 || d < 1 || N_kv < 1 || kv_row_stride < N_kv) return -1;
+    if (frame_T < 1 || N_q % frame_T != 0 || denoise_row0 < 0 || denoise_row0 + N_q > N_kv) return -1;
+    if (!rows) n_rows = N_q;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)N_kv);
+        double *q = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!z || !q) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 4)
+            for (int h = 0; h < H; ++h)
+                for (int64_t r = 0; r < n_rows; ++r) {
+                    int64_t qi = rows ? rows[r] : r;
+                    int64_t q_frame = qi / frame_T;
+                    for (int c = 0; c < d; ++c) q[c] = load_elem(Q, dtype, ((size_t)h * N_q + qi) * d + c);
+                    double zmax = -INFINITY;
+                    for (int64_t n = 0; n < N_kv; ++n) {
+                        int inside = n >= denoise_row0 && n < denoise_row0 + N_q;
+                        if (inside && (n - denoise_row0) / frame_T > q_frame) {
+                            z[n] = -INFINITY;   /* a later frame of the same chunk: not visible */
+                            continue;
+                        }
+                        size_t base = ((size_t)h * kv_row_stride + n) * d;
+                        double dot = 0.0;
+                        for (int c = 0; c < d; ++c) dot += q[c] * load_elem(K, dtype, base + c);
+                        z[n] = dot * scale;
+                        if (z[n] > zmax) zmax = z[n];
+                    }
+                    double denom = 0.0;
+                    for (int64_t n = 0; n < N_kv; ++n) {
+                        z[n] = z[n] == -INFINITY ? 0.0 : exp(z[n] - zmax);
+                        denom += z[n];
+                    }
+                    double *o = O + ((size_t)h * n_rows + r) * d;
+                    for (int c = 0; c < d; ++c) o[c] = 0.0;
+                    for (int64_t n = 0; n < N_kv; ++n) {
+                        if (z[n] == 0.0) continue;
                         size_t base = ((size_t)h * kv_row_stride + n) * d;
                         double p = z[n] / denom;
                         for (int c = 0; c < d; ++c) o[c] += p * load_elem(V, dtype, base + c);

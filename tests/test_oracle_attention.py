@@ -151,3 +151,66 @@ def test_retrieving_everything_uncompressed_is_full_kv_attention():
     K_full = torch.cat([Kn] + [c[0] for c in chunks], 1)    # history in generation order
     V_full = torch.cat([Vn] + [c[1] for c in chunks], 1)
     np.testing.assert_allclose(got, oracle.attention(Q, K_full, V_full), rtol=0, atol=1e-13)
+
+
+# ---- frame-level causal mask inside the denoising chunk (an option; the paper states no mask) ----
+
+def _bc_setup(seed, H=2, T=5, F=3, n_before=7, n_after=9, d=16):
+    g = torch.Generator().manual_seed(seed)
+    N_q = F * T
+    N_kv = n_before + N_q + n_after
+    Q = torch.randn(H, N_q, d, generator=g)
+    K = torch.randn(H, N_kv, d, generator=g)
+    V = torch.randn(H, N_kv, d, generator=g)
+    return Q, K, V, n_before, T, F
+
+
+def test_block_causal_against_library_masked_softmax():
+    for seed, (nb, na) in enumerate([(7, 9), (0, 9), (7, 0), (0, 0)]):
+        Q, K, V, row0, T, F = _bc_setup(seed, n_before=nb, n_after=na)
+        H, N_q, d = Q.shape
+        N_kv = K.shape[1]
+        O, lse = oracle.attention_block_causal(Q, K, V, row0, T, want_lse=True)
+        z = torch.einsum("hqd,hkd->hqk", Q.double(), K.double()) / math.sqrt(d)
+        qf = (torch.arange(N_q) // T).view(N_q, 1)
+        kpos = torch.arange(N_kv).view(1, N_kv)
+        inside = (kpos >= row0) & (kpos < row0 + N_q)
+        hidden = inside & (((kpos - row0) // T) > qf)
+        z = z.masked_fill(hidden.unsqueeze(0), float("-inf"))
+        ref = torch.softmax(z, -1) @ V.double()
+        np.testing.assert_allclose(O, ref.numpy(), atol=1e-13)
+        np.testing.assert_allclose(lse, torch.logsumexp(z, -1).numpy(), atol=1e-13)
+        # the count of visible keys per query frame: everything but the later frames of its own chunk
+        vis = (~hidden).sum(1)
+        assert vis.tolist() == [N_kv - (F - 1 - int(f)) * T for f in qf.view(-1)]
+
+
+def test_block_causal_reduces_to_plain_attention_on_reduced_windows():
+    Q, K, V, row0, T, F = _bc_setup(5)
+    N_q = F * T
+    O = oracle.attention_block_causal(Q, K, V, row0, T)
+    for f in range(F):
+        rows = np.arange(f * T, (f + 1) * T)
+        # frame f sees the window with the later frames of the chunk cut out
+        keep = [n for n in range(K.shape[1]) if not (row0 + (f + 1) * T <= n < row0 + N_q)]
+        ref = oracle.attention(Q, K[:, keep].contiguous(), V[:, keep].contiguous(), rows=rows)
+        np.testing.assert_allclose(O[:, rows], ref, atol=1e-13)
+    # the last frame sees everything: plain attention
+    last = np.arange((F - 1) * T, N_q)
+    np.testing.assert_allclose(O[:, last], oracle.attention(Q, K, V, rows=last), atol=1e-13)
+    # one frame per chunk: the mask hides nothing
+    np.testing.assert_allclose(oracle.attention_block_causal(Q, K, V, row0, N_q), oracle.attention(Q, K, V), atol=1e-13)
+    # frames of one token: a plain causal mask inside the chunk; the first query sees exactly one chunk key
+    Qs, Ks, Vs = Q[:, :4].contiguous(), K[:, :4].contiguous(), V[:, :4].contiguous()
+    O1 = oracle.attention_block_causal(Qs, Ks, Vs, 0, 1)
+    np.testing.assert_allclose(O1[:, 0], Vs[:, 0].double().numpy(), atol=1e-13)
+    # row subsets and lse agree with the full call
+    sub = np.array([0, 4, 5, 14], np.int32)
+    Os, ls = oracle.attention_block_causal(Q, K, V, row0, T, rows=sub, want_lse=True)
+    Of, lf = oracle.attention_block_causal(Q, K, V, row0, T, want_lse=True)
+    np.testing.assert_allclose(Os, Of[:, sub], atol=0)
+    np.testing.assert_allclose(ls, lf[:, sub], atol=0)
+    with pytest.raises(ValueError):
+        oracle.attention_block_causal(Q, K, V, row0, 4)            # N_q not a multiple of the frame
+    with pytest.raises(ValueError):
+        oracle.attention_block_causal(Q, K, V, K.shape[1] - 3, T)  # chunk rows run past the window
