@@ -206,6 +206,20 @@ def main():
         "gather_hbm_GBps": gather_bytes / (per_call["gather_hbm"] * 1e-3) / 1e9,
     }
 
+    if cfg.q_frames > 1 and N_kv >= 2 * cfg.N_q:
+        # option: frame-level causal mask inside the denoising chunk, placed behind a sink chunk of the same
+        # size (the window manager's layout); same window, so the flop count is that of the unmasked call
+        # minus the hidden later frames
+        bc_ws = torch.empty(wk.wk_attention_block_causal_workspace_bytes(cfg.H, cfg.N_q), dtype=torch.uint8,
+                            device=dev)
+        t_bc = time_call(lambda: wk.wk_attention_block_causal(Q, Kw, Vw, O, cfg.N_q, cfg.T, bc_ws, N_kv=N_kv,
+                                                              n_kv_dev=n_win), 3)
+        hidden = sum(cfg.q_frames - 1 - f for f in range(cfg.q_frames)) * cfg.T * cfg.T
+        bc_flops = flops - 4.0 * hidden * cfg.d * cfg.H
+        extra["attention_block_causal"] = {"ms": t_bc, "tflops": bc_flops / (t_bc * 1e-3) / 1e12,
+                                           "launches": cfg.q_frames + 2}
+        del bc_ws
+
     if cfg.M > 0 and cfg.M <= wk.WK_QUERY_MAX_CHUNKS:
         # query-based retrieval (Sec. 4.2, App. C) in place of the pose distance: attention mass of the
         # current queries on every stored chunk, over a device-resident index of the chunks' anchor keys

@@ -225,6 +225,26 @@ wk_status wk_attention(const void *Q, const void *K_win, const void *V_win, void
 /* Bytes of workspace with which wk_attention splits the key range for this shape (0: it would not). */
 size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype);
 
+/* wk_attention with a frame-level causal mask inside the chunk being denoised -- an option; the
+ * paper's method itself states no mask (Sec. 4.2), frame-causal attention inside a chunk is a
+ * property some of the autoregressive video backbones of Sec. 3 have.  The N_q queries are the
+ * chunk's tokens, N_q / frame_T frames of frame_T tokens, and their own keys are window rows
+ * [denoise_row0, denoise_row0 + N_q) in the same order (wk_window_step.denoise_row0).  Query i
+ * sees every window row outside that range and, inside it, the rows of frames 0 .. i / frame_T.
+ * Arguments as for wk_attention; O is required.
+ *
+ *   n_kv_dev   if given, *n_kv_dev must be >= denoise_row0 + N_q (the chunk lies inside the window)
+ *   workspace  device, 256-byte aligned, wk_attention_block_causal_workspace_bytes(H, N_q) bytes:
+ *              the two visible key ranges of a query are attended separately and merged
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128), SHAPE (N_kv, or N_q not a multiple of frame_T, or
+ * the chunk's rows run past N_kv), WORKSPACE. */
+wk_status wk_attention_block_causal(const void *Q, const void *K_win, const void *V_win, void *O,
+                                    float *lse, int32_t H, int32_t N_q, int32_t N_kv, int32_t d,
+                                    int32_t kv_row_stride, int32_t dtype, float scale,
+                                    const int32_t *n_kv_dev, int32_t denoise_row0, int32_t frame_T,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t wk_attention_block_causal_workspace_bytes(int32_t H, int32_t N_q);
+
 /* First half of query-based retrieval (Sec. 4.2, App. C): the log-sum-exp of the current queries'
  * scaled logits against the stored keys of every chunk of the store, all chunks in one launch.
  * The result is the `lse` input of wk_score_chunks_query.  Only K_ptr, n_tok, M, H, d and dtype

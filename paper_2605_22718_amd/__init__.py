@@ -27,6 +27,7 @@ WK_QUERY_MAX_CHUNKS = 1024
 EXPORTS = [
     "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
     "wk_score_chunks_query", "wk_score_chunks_query_workspace_bytes", "wk_chunk_lse",
+    "wk_attention_block_causal", "wk_attention_block_causal_workspace_bytes",
     "wk_window_plan", "wk_window_update", "wk_window_update_workspace_bytes",
     "wk_prefetch_create", "wk_prefetch_destroy", "wk_prefetch_stream", "wk_prefetch_after", "wk_prefetch_gather",
     "wk_prefetch_acquire", "wk_prefetch_release",
@@ -119,6 +120,11 @@ def lib():
         L.wk_prefetch_acquire.argtypes = [vp, i32, vp]
         L.wk_prefetch_release.restype = C.c_int
         L.wk_prefetch_release.argtypes = [vp, i32, vp]
+        L.wk_attention_block_causal.restype = C.c_int
+        L.wk_attention_block_causal.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp, i32, i32,
+                                                vp, C.c_size_t, vp]
+        L.wk_attention_block_causal_workspace_bytes.restype = C.c_size_t
+        L.wk_attention_block_causal_workspace_bytes.argtypes = [i32, i32]
         L.wk_attention_workspace_bytes.restype = C.c_size_t
         L.wk_attention_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.wk_host_device_pointer.restype = C.c_int
@@ -264,6 +270,26 @@ def wk_gather_window(store_desc: wk_store_desc, ids, n_ids, R_max, K_native, V_n
                                 _dev(V_native, "V_native"), n_native, _dev(K_win, "K_win"), _dev(V_win, "V_win"),
                                 win_capacity, _dev(n_win, "n_win", torch.int32), _stream())
     _check(st, "wk_gather_window")
+
+
+def wk_attention_block_causal_workspace_bytes(H, N_q) -> int:
+    return lib().wk_attention_block_causal_workspace_bytes(H, N_q)
+
+
+def wk_attention_block_causal(Q, K_win, V_win, O, denoise_row0, frame_T, workspace, lse=None, N_kv=None, scale=0.0,
+                              n_kv_dev=None):
+    """wk_attention_block_causal.  The chunk's own keys are window rows [denoise_row0, denoise_row0 + N_q)."""
+    H, N_q, d = Q.shape
+    stride = K_win.shape[1]
+    N_kv = stride if N_kv is None else N_kv
+    st = lib().wk_attention_block_causal(_dev(Q, "Q"), _dev(K_win, "K_win", Q.dtype), _dev(V_win, "V_win", Q.dtype),
+                                         _dev(O, "O", Q.dtype), _dev(lse, "lse", torch.float32), H, N_q, N_kv, d,
+                                         stride, dtype_code(Q), scale, _dev(n_kv_dev, "n_kv_dev", torch.int32),
+                                         denoise_row0, frame_T, _dev(workspace, "workspace"),
+                                         0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                         _stream())
+    _check(st, "wk_attention_block_causal")
+    return O
 
 
 def wk_chunk_lse(store_desc: wk_store_desc, Q, lse_out, scale=0.0):

@@ -45,6 +45,11 @@ struct AttnArgs {
     const void *const *k_table;
     const int32_t *n_tok;
     int n_chunks;
+    // a launch may cover queries [q_off, q_off + N_q) of arrays that hold q_rows rows per head
+    // (Q, O, lse and the partial results), and a key range that starts kv_start rows into the
+    // window (only used to convert *n_kv_dev); part_slot >= 0 makes it write its (O, max, sum)
+    // as split `part_slot` for k_attn_merge instead of a final result.
+    int q_rows, q_off, kv_start, part_slot;
 };
 
 constexpr int kXcds = 8;
@@ -91,14 +96,14 @@ __device__ inline Window window_of(const AttnArgs &a, int c) {
     if (a.n_chunks > 0) {
         w.K = reinterpret_cast<const char *>(a.k_table[c]);
         w.n_kv = w.stride = a.n_tok[c];
-        w.lse = a.lse + (size_t)c * a.H * a.N_q;
+        w.lse = a.lse + (size_t)c * a.H * a.q_rows;
     } else {
         w.K = a.K;
         w.stride = a.kv_row_stride;
         w.lse = a.lse;
         w.n_kv = a.N_kv;
         if (a.n_kv_dev) {
-            const int m = *a.n_kv_dev;
+            const int m = *a.n_kv_dev - a.kv_start;
             w.n_kv = m < w.n_kv ? m : w.n_kv;
         }
     }
@@ -127,15 +132,22 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
     const int q = qt * (kF32Waves * 32) + wave * 32 + col;
     const bool q_ok = q < a.N_q;
     const int q_ld = q_ok ? q : a.N_q - 1;
-    const float *Qrow = reinterpret_cast<const float *>(a.Q) + ((size_t)h * a.N_q + q_ld) * WK_D;
-    float *Orow = reinterpret_cast<float *>(a.O) + ((size_t)h * a.N_q + q_ld) * WK_D;
+    const size_t qrow = (size_t)h * a.q_rows + a.q_off + q_ld;   // row of this lane's query in Q / O / lse
+    const float *Qrow = reinterpret_cast<const float *>(a.Q) + qrow * WK_D;
+    float *Orow = reinterpret_cast<float *>(a.O) + qrow * WK_D;
     const bool with_o = a.O != nullptr;   // false: log-sum-exp only, V is not read (zeros stand in)
+    const bool partial_out = a.part_slot >= 0;
+    const size_t prow = ((size_t)(partial_out ? a.part_slot : 0) * a.H + h) * a.q_rows + a.q_off + q_ld;
 
     if (n_kv == 0) {
-        if (q_ok) {
+        if (q_ok && partial_out) {
+            for (int c = g * 64; c < g * 64 + 64; c += 4)
+                *reinterpret_cast<float4 *>(a.part_o + prow * WK_D + c) = float4{0, 0, 0, 0};
+            if (g == 0) { a.part_ml[prow * 2] = -INFINITY; a.part_ml[prow * 2 + 1] = 0.f; }
+        } else if (q_ok) {
             if (with_o)
                 for (int c = g * 64; c < g * 64 + 64; c += 4) *reinterpret_cast<float4 *>(Orow + c) = float4{0, 0, 0, 0};
-            if (lse && g == 0) lse[(size_t)h * a.N_q + q] = -INFINITY;
+            if (lse && g == 0) lse[qrow] = -INFINITY;
         }
         return;
     }
@@ -217,7 +229,16 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
         }
     }
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (q_ok) {
+    if (q_ok && partial_out) {   // (O, max, sum) of this key range, merged by k_attn_merge
+        float *Po = a.part_o + prow * WK_D;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                *reinterpret_cast<float4 *>(Po + 32 * b + 8 * t + 4 * g) =
+                    float4{o[b][4 * t], o[b][4 * t + 1], o[b][4 * t + 2], o[b][4 * t + 3]};
+        if (g == 0) { a.part_ml[prow * 2] = m_run; a.part_ml[prow * 2 + 1] = l_tot; }
+    } else if (q_ok) {
         const float inv = 1.f / l_tot;
         if (with_o)
 #pragma unroll
@@ -228,7 +249,7 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
                 *reinterpret_cast<float4 *>(Orow + dv) =
                     float4{o[b][4 * t] * inv, o[b][4 * t + 1] * inv, o[b][4 * t + 2] * inv, o[b][4 * t + 3] * inv};
             }
-        if (lse && g == 0) lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        if (lse && g == 0) lse[qrow] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 
@@ -278,7 +299,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     const int q = qt * (WAVES * 32) + wave * 32 + col;
     const bool q_ok = q < a.N_q;
     const int q_ld = q_ok ? q : a.N_q - 1;
-    const char *Qrow = a.Q + ((size_t)h * a.N_q + q_ld) * 256;
+    const char *Qrow = a.Q + ((size_t)h * a.q_rows + a.q_off + q_ld) * 256;
+    const bool partial_out = a.splits > 1 || a.part_slot >= 0;  // (O, max, sum) for k_attn_merge
+    // rows of this lane's query in O / lse and in the partial arrays (formed where they are used:
+    // two 64-bit values per lane are not worth carrying through the loop)
+    auto out_row = [&]() { return (size_t)h * a.q_rows + a.q_off + q; };
+    auto part_row = [&]() { return ((size_t)(a.part_slot >= 0 ? a.part_slot : sp) * a.H + h) * a.q_rows + a.q_off + q; };
 
     // this workgroup's tiles [t0, t1) of the window
     const int n_tiles = (n_kv + kKeys - 1) / kKeys;
@@ -287,14 +313,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     const int t1 = min(n_tiles, t0 + tiles_per_split);
     if (t0 >= t1) {   // empty window, or a split past its end: contributes nothing
         if (q_ok) {
-            if (a.splits == 1) {
-                char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+            if (!partial_out) {
+                const size_t qrow = out_row();
+                char *Orow = a.O + qrow * 256;
                 for (int c = g * 8; c < g * 8 + 8; ++c) reinterpret_cast<uint4 *>(Orow)[c] = uint4{0, 0, 0, 0};
-                if (lse && g == 0) lse[(size_t)h * a.N_q + q] = -INFINITY;
+                if (lse && g == 0) lse[qrow] = -INFINITY;
             } else {
-                const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
-                for (int c = g * 16; c < g * 16 + 16; ++c) reinterpret_cast<float4 *>(a.part_o + row * WK_D)[c] = float4{0, 0, 0, 0};
-                if (g == 0) { a.part_ml[row * 2] = -INFINITY; a.part_ml[row * 2 + 1] = 0.f; }
+                const size_t prow = part_row();
+                for (int c = g * 16; c < g * 16 + 16; ++c) reinterpret_cast<float4 *>(a.part_o + prow * WK_D)[c] = float4{0, 0, 0, 0};
+                if (g == 0) { a.part_ml[prow * 2] = -INFINITY; a.part_ml[prow * 2 + 1] = 0.f; }
             }
         }
         return;
@@ -507,8 +534,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped look-ahead loads before the LDS is released
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (q_ok && a.splits == 1) {
-        char *Orow = a.O + ((size_t)h * a.N_q + q) * 256;
+    if (q_ok && !partial_out) {
+        const size_t qrow = out_row();
+        char *Orow = a.O + qrow * 256;
         const float inv = 1.f / l_tot;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
@@ -522,17 +550,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
                 w.y = __builtin_bit_cast(uint32_t, hi);
                 *reinterpret_cast<uint2 *>(Orow + dv * 2) = w;
             }
-        if (lse && g == 0) lse[(size_t)h * a.N_q + q] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        if (lse && g == 0) lse[qrow] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
     } else if (q_ok) {   // partial result of this key range, merged by k_attn_merge
-        const size_t row = ((size_t)sp * a.H + h) * a.N_q + q;
-        float *Po = a.part_o + row * WK_D;
+        const size_t prow = part_row();
+        float *Po = a.part_o + prow * WK_D;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 *reinterpret_cast<float4 *>(Po + 32 * b + 8 * t + 4 * g) =
                     float4{o[b][4 * t], o[b][4 * t + 1], o[b][4 * t + 2], o[b][4 * t + 3]};
-        if (g == 0) { a.part_ml[row * 2] = m_run; a.part_ml[row * 2 + 1] = l_tot; }
+        if (g == 0) { a.part_ml[prow * 2] = m_run; a.part_ml[prow * 2 + 1] = l_tot; }
     }
 }
 
@@ -558,8 +586,8 @@ __global__ __launch_bounds__(512, 4) void k_lse_bf16(AttnArgs a) {
     const int q = qt * 256 + wave * 32 + col;
     const bool q_ok = q < a.N_q;
     const int q_ld = q_ok ? q : a.N_q - 1;
-    const char *Qrow = a.Q + ((size_t)h * a.N_q + q_ld) * 256;
-    float *const out = win.lse + (size_t)h * a.N_q + q;
+    const char *Qrow = a.Q + ((size_t)h * a.q_rows + a.q_off + q_ld) * 256;
+    float *const out = win.lse + (size_t)h * a.q_rows + a.q_off + q;
     if (n_kv == 0) {
         if (q_ok && g == 0) *out = -INFINITY;
         return;
@@ -685,10 +713,11 @@ __global__ __launch_bounds__(512, 4) void k_lse_bf16(AttnArgs a) {
 
 // Merge of the key-range splits: O = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s, m = max_s m_s.
 // 16 lanes per query row, 8 features each; fixed summation order.
+template <int DT>
 __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
-    const size_t row = (size_t)blockIdx.x * 16 + threadIdx.x / 16;   // h * N_q + q
+    const size_t row = (size_t)blockIdx.x * 16 + threadIdx.x / 16;   // h * q_rows + q
     const int sub = threadIdx.x % 16;
-    const size_t rows = (size_t)a.H * a.N_q;
+    const size_t rows = (size_t)a.H * a.q_rows;
     if (row >= rows) return;
     float m = -INFINITY;
     for (int s = 0; s < a.splits; ++s) m = fmaxf(m, a.part_ml[((size_t)s * rows + row) * 2]);
@@ -705,12 +734,18 @@ __global__ __launch_bounds__(256) void k_attn_merge(AttnArgs a) {
         acc[4] = fmaf(w, y.x, acc[4]); acc[5] = fmaf(w, y.y, acc[5]); acc[6] = fmaf(w, y.z, acc[6]); acc[7] = fmaf(w, y.w, acc[7]);
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    uint4 out;
-    uint32_t *ow = reinterpret_cast<uint32_t *>(&out);
+    if constexpr (DT == WK_BF16) {
+        uint4 out;
+        uint32_t *ow = reinterpret_cast<uint32_t *>(&out);
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-        ow[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{acc[2 * e] * inv, acc[2 * e + 1] * inv}, bf16x2));
-    reinterpret_cast<uint4 *>(a.O + row * 256)[sub] = out;
+        for (int e = 0; e < 4; ++e)
+            ow[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{acc[2 * e] * inv, acc[2 * e + 1] * inv}, bf16x2));
+        reinterpret_cast<uint4 *>(a.O + row * 256)[sub] = out;
+    } else {
+        float4 *po = reinterpret_cast<float4 *>(a.O + row * 512) + 2 * sub;
+        po[0] = float4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+        po[1] = float4{acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv};
+    }
     if (a.lse && sub == 0) a.lse[row] = l > 0.f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
@@ -759,7 +794,7 @@ wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipSt
     WK_LAUNCH_CHECK();
     if (a.splits > 1) {
         const size_t rows = (size_t)a.H * a.N_q;
-        hipLaunchKernelGGL(k_attn_merge, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k_attn_merge<WK_BF16>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
         WK_LAUNCH_CHECK();
     }
     return WK_OK;
@@ -795,6 +830,7 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     a.k_table = nullptr;
     a.n_tok = nullptr;
     a.n_chunks = 0;
+    a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     if (dtype == WK_F32) {
         const int q_per_wg = kF32Waves * 32;
@@ -806,6 +842,105 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
         return WK_OK;
     }
     return launch_bf16<8>(a, workspace, workspace_bytes, st);
+}
+
+namespace {
+
+// One launch of the attention kernel for the dtype, exactly as the arguments say: no choice of
+// key-range splits, no merge.
+wk_status launch_plain(AttnArgs a, int dtype, hipStream_t st) {
+    a.splits = 1;
+    if (dtype == WK_F32) {
+        a.n_qtiles = (a.N_q + kF32Waves * 32 - 1) / (kF32Waves * 32);
+        a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
+        hipLaunchKernelGGL(k_attn_f32, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a);
+    } else {
+        a.n_qtiles = (a.N_q + 255) / 256;
+        a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
+            return WK_ERR_HIP;
+        hipLaunchKernelGGL(k_attn_bf16<8>, dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a);
+    }
+    WK_LAUNCH_CHECK();
+    return WK_OK;
+}
+
+}  // namespace
+
+extern "C" size_t wk_attention_block_causal_workspace_bytes(int32_t H, int32_t N_q) {
+    if (H < 1 || N_q < 1) return 0;
+    return split_workspace_bytes(H, N_q, 2);
+}
+
+// Frame-level causal mask inside the chunk being denoised, as two key ranges per query frame
+// whose partial (O, max, sum) results k_attn_merge combines: range A = window rows up to and
+// including the query's own frame of the chunk (one launch per frame: all its queries share the
+// range), range B = the rows behind the chunk (one launch for all queries).  The kernels run
+// unchanged; they are only told which queries, which rows and which partial slot.
+extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win, const void *V_win, void *O,
+                                               float *lse, int32_t H, int32_t N_q, int32_t N_kv, int32_t d,
+                                               int32_t kv_row_stride, int32_t dtype, float scale,
+                                               const int32_t *n_kv_dev, int32_t denoise_row0, int32_t frame_T,
+                                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!Q || !K_win || !V_win || !O) return WK_ERR_INVALID_ARG;
+    if (H < 1 || N_q < 0 || d < 1 || frame_T < 1 || denoise_row0 < 0) return WK_ERR_INVALID_ARG;
+    if (dtype != WK_F32 && dtype != WK_BF16) return WK_ERR_INVALID_ARG;
+    if (!(scale >= 0.f) || std::isinf(scale)) return WK_ERR_INVALID_ARG;
+    if (d != WK_D) return WK_ERR_UNSUPPORTED;
+    if (N_kv < 1 || N_kv > kv_row_stride) return WK_ERR_SHAPE;
+    if (N_q % frame_T != 0 || (int64_t)denoise_row0 + N_q > (int64_t)N_kv) return WK_ERR_SHAPE;
+    if (N_q == 0) return WK_OK;
+    if (!workspace || workspace_bytes < split_workspace_bytes(H, N_q, 2) ||
+        reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return WK_ERR_WORKSPACE;
+    const size_t row_bytes = WK_D * wk::esize(dtype);
+    AttnArgs a;
+    a.Q = reinterpret_cast<const char *>(Q);
+    a.K = reinterpret_cast<const char *>(K_win);
+    a.V = reinterpret_cast<const char *>(V_win);
+    a.O = reinterpret_cast<char *>(O);
+    a.lse = lse;
+    a.H = H; a.N_q = N_q; a.N_kv = N_kv; a.kv_row_stride = kv_row_stride;
+    const float sc = scale == 0.f ? 1.f / std::sqrt((float)d) : scale;
+    a.scale_log2 = sc * 1.4426950408889634f;
+    a.n_kv_dev = n_kv_dev;
+    a.splits = 1;
+    a.part_o = reinterpret_cast<float *>(workspace);
+    a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                          wk::align_up((size_t)2 * H * N_q * WK_D * sizeof(float), 256));
+    a.k_table = nullptr; a.n_tok = nullptr; a.n_chunks = 0;
+    a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+
+    AttnArgs b = a;   // the rows behind the chunk, every query
+    const int start = denoise_row0 + N_q;
+    b.K += (size_t)start * row_bytes;
+    b.V += (size_t)start * row_bytes;
+    b.N_kv = N_kv - start;
+    b.kv_start = start;
+    b.part_slot = 1;
+    wk_status rc = launch_plain(b, dtype, st);
+    if (rc != WK_OK) return rc;
+    const int frames = N_q / frame_T;
+    for (int f = 0; f < frames; ++f) {   // rows up to the end of frame f of the chunk, that frame's queries
+        AttnArgs p = a;
+        p.N_q = frame_T;
+        p.q_off = f * frame_T;
+        p.N_kv = denoise_row0 + (f + 1) * frame_T;
+        p.part_slot = 0;
+        rc = launch_plain(p, dtype, st);
+        if (rc != WK_OK) return rc;
+    }
+    AttnArgs m = a;
+    m.splits = 2;
+    const size_t rows = (size_t)H * N_q;
+    if (dtype == WK_F32)
+        hipLaunchKernelGGL(k_attn_merge<WK_F32>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, m);
+    else
+        hipLaunchKernelGGL(k_attn_merge<WK_BF16>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, m);
+    WK_LAUNCH_CHECK();
+    return WK_OK;
 }
 
 extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int32_t N_q, float scale,
@@ -832,6 +967,7 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
     a.k_table = store->K_ptr;
     a.n_tok = store->n_tok;
     a.n_chunks = store->M;
+    a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int q_per_wg = (store->dtype == WK_F32 ? kF32Waves : 8) * 32;
     const long long items = (long long)store->M * store->H * ((N_q + q_per_wg - 1) / q_per_wg);

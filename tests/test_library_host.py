@@ -150,6 +150,20 @@ def test_argument_validation_of_the_other_calls():
     assert L.wk_prefetch_acquire(None, 0, None) == wk.WK_ERR_INVALID_ARG
     assert L.wk_prefetch_release(None, 0, None) == wk.WK_ERR_INVALID_ARG
     assert L.wk_prefetch_gather(None, 0, C.byref(sd), one, None, 2, one, one, 5, one, one, 64, None, 0) == wk.WK_ERR_INVALID_ARG
+    # block-causal attention
+    def bc(**kw):
+        a = dict(dict(N_q=6, N_kv=20, row0=4, T=3, ws=one, ws_bytes=1 << 20, d=128), **kw)
+        return L.wk_attention_block_causal(one, one, one, one, None, 2, a["N_q"], a["N_kv"], a["d"], 32, 1, 0.0, None,
+                                           a["row0"], a["T"], a["ws"], a["ws_bytes"], None)
+    assert bc(T=0) == wk.WK_ERR_INVALID_ARG
+    assert bc(row0=-1) == wk.WK_ERR_INVALID_ARG
+    assert bc(d=64) == wk.WK_ERR_UNSUPPORTED
+    assert bc(T=4) == wk.WK_ERR_SHAPE             # N_q is not a multiple of the frame
+    assert bc(row0=15) == wk.WK_ERR_SHAPE         # the chunk's rows run past the window
+    assert bc(N_kv=40) == wk.WK_ERR_SHAPE         # beyond the row stride
+    assert bc(ws=None) == wk.WK_ERR_WORKSPACE
+    assert bc(ws_bytes=100) == wk.WK_ERR_WORKSPACE
+    assert wk.wk_attention_block_causal_workspace_bytes(2, 6) >= 2 * 2 * 6 * (128 + 2) * 4
     # key-range splits are only proposed when the plain grid would leave compute units idle
     assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
     assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4
