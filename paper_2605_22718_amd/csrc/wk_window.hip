@@ -26,6 +26,8 @@ constexpr int kThreads = 256;
 constexpr int kVecPerThread = 8;
 constexpr int kVecPerBlock = kThreads * kVecPerThread;
 
+typedef unsigned int uvec4 __attribute__((ext_vector_type(4)));   // a 16-byte vector the nontemporal builtins accept
+
 struct PlanOut {   // head of the workspace
     int32_t n_fetch;
     int32_t n_used;
@@ -155,16 +157,16 @@ __global__ __launch_bounds__(kThreads) void k_slot_fetch(FetchArgs a) {
                           (size_t)h * a.slot_tokens * row_bytes;
         char *dst = (is_v ? a.V_win : a.K_win) +
                     ((size_t)h * a.win_capacity + a.n_native + (size_t)slot * a.slot_tokens) * row_bytes;
-        uint4 buf[kVecPerThread];
+        uvec4 buf[kVecPerThread];
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
             const long long v = v0 + tid + (long long)i * kThreads;
-            if (v < slot_vec) buf[i] = *reinterpret_cast<const uint4 *>(src + (size_t)v * 16);
+            if (v < slot_vec) buf[i] = __builtin_nontemporal_load(reinterpret_cast<const uvec4 *>(src) + v);
         }
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
             const long long v = v0 + tid + (long long)i * kThreads;
-            if (v < slot_vec) *reinterpret_cast<uint4 *>(dst + (size_t)v * 16) = buf[i];
+            if (v < slot_vec) __builtin_nontemporal_store(buf[i], reinterpret_cast<uvec4 *>(dst) + v);
         }
     }
 }
