@@ -570,7 +570,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
 // by the VALU, not by the matrix cores.  It therefore drops the in-wave software pipeline of
 // k_attn_bf16 (two S^T tiles in registers) for occupancy: under 128 VGPRs and with a 64 KB K
 // ring, two workgroups = four waves per SIMD share a CU, and one wave's MFMAs run under the
-// others' exp2.  Same tile layout, loads and arithmetic (bf16-rounded probabilities summed by
+// others' exp2; the workgroup's waves meet at a barrier only every second tile.  Same tile layout,
+// loads and arithmetic (bf16-rounded probabilities summed by
 // dot2) as the full kernel: the lse values are bit-identical to those wk_attention returns
 // beside O.
 // ------------------------------------------------------------------------------------------
@@ -672,39 +673,51 @@ __global__ __launch_bounds__(512, 4) void k_lse_bf16(AttnArgs a) {
             }
     };
     const int n_full = n_kv / kKeys;   // full tiles; one partial tile may follow
+    const bool tail = n_full * kKeys < n_kv;
     issue_tile(0, 0);
     issue_tile(1, 1);
-    issue_tile(2, 2);
-    // step j: tile j of every wave has landed (vmcnt(4) leaves tiles j+1, j+2 in flight) and every
-    // wave is done with tile j-1, whose slot tile j+3 may now overwrite
-    auto step = [&](int j, auto pos_tag, bool partial) {
+    // One barrier per two tiles.  Before it, this wave's loads of tiles j and j+1 have landed
+    // (vmcnt(0): nothing newer is in flight yet); behind it every wave is done with tiles j-2 and
+    // j-1, whose slots tiles j+2 and j+3 may overwrite.
+    auto open_pair = [&](int j, auto pos_tag) {
         constexpr int POS = decltype(pos_tag)::value;
-        __builtin_amdgcn_s_waitcnt(0x0F74);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
+        issue_tile(j + 2, (POS + 2) & 3);
         issue_tile(j + 3, (POS + 3) & 3);
-        tile(POS * kTileBytes, j * kKeys, partial);
     };
     using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
     using P2 = std::integral_constant<int, 2>;
-    using P3 = std::integral_constant<int, 3>;
+    auto full_pair = [&](int j, auto pos_tag) {
+        constexpr int POS = decltype(pos_tag)::value;
+        open_pair(j, pos_tag);
+        tile(POS * kTileBytes, j * kKeys, false);
+        tile((POS + 1) * kTileBytes, (j + 1) * kKeys, false);
+    };
+    // what is left after the full pairs: at most one full tile and the partial one
+    auto last_pair = [&](int j, auto pos_tag, int full) {
+        constexpr int POS = decltype(pos_tag)::value;
+        open_pair(j, pos_tag);
+        if (full) {
+            tile(POS * kTileBytes, j * kKeys, false);
+            if (tail) tile((POS + 1) * kTileBytes, (j + 1) * kKeys, true);
+        } else {
+            tile(POS * kTileBytes, j * kKeys, true);
+        }
+    };
     int j = 0;
     for (; j + 4 <= n_full; j += 4) {
-        step(j, P0{}, false);
-        step(j + 1, P1{}, false);
-        step(j + 2, P2{}, false);
-        step(j + 3, P3{}, false);
+        full_pair(j, P0{});
+        full_pair(j + 2, P2{});
     }
-    const int rest = n_full - j;   // 0..3 full tiles, then perhaps the partial one, at positions 0, 1, ...
-    const bool tail = n_full * kKeys < n_kv;
-    if (rest > 0) step(j, P0{}, false);
-    if (rest > 1) step(j + 1, P1{}, false);
-    if (rest > 2) step(j + 2, P2{}, false);
-    if (tail) {
-        if (rest == 0) step(j, P0{}, true);
-        else if (rest == 1) step(j + 1, P1{}, true);
-        else if (rest == 2) step(j + 2, P2{}, true);
-        else step(j + 3, P3{}, true);
+    int rest = n_full - j;   // 0..3 full tiles, then perhaps the partial one
+    if (rest >= 2) {
+        full_pair(j, P0{});
+        j += 2;
+        rest -= 2;
+        if (rest || tail) last_pair(j, P2{}, rest);
+    } else if (rest || tail) {
+        last_pair(j, P0{}, rest);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped look-ahead loads before the LDS is released
     const float l_tot = l_run + __shfl_xor(l_run, 32);
