@@ -165,6 +165,21 @@ def main():
     flops = 4.0 * cfg.N_q * N_kv * cfg.d * cfg.H
     att_tflops = flops / (att_ms * 1e-3) / 1e12
 
+    # the same step captured once in a HIP graph and replayed (no per-call host work)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(store.desc)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_step_graph = (time.perf_counter() - t0) / a.steps * 1e3
+    assert int(n_win.item()) == N_kv
+
     # per-call times (each call alone on the stream, HIP events, mean of `steps` repetitions)
     def time_call(fn, reps):
         fn()
@@ -203,6 +218,7 @@ def main():
         "attention_tflops": att_tflops,
         "pct_bf16_mfma_peak": 100.0 * att_tflops / PEAK_BF16_TFLOPS,
         "ms_per_chunk": per_call,
+        "ms_per_step_graph_replay": ms_step_graph,
         "gather_hbm_GBps": gather_bytes / (per_call["gather_hbm"] * 1e-3) / 1e9,
     }
 

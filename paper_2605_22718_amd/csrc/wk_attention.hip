@@ -780,6 +780,19 @@ size_t split_workspace_bytes(int H, int N_q, int splits) {
     return wk::align_up(rows * WK_D * sizeof(float), 256) + wk::align_up(rows * 2 * sizeof(float), 256);
 }
 
+// k_attn_bf16 uses more than the default 64 KB of dynamic LDS: raise its limit once per process
+// (not a stream operation, so a first call under graph capture is fine too).
+wk_status allow_large_lds() {
+    static bool done = false;
+    if (!done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
+            return WK_ERR_HIP;
+        done = true;
+    }
+    return WK_OK;
+}
+
 template <int WAVES>
 wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipStream_t st) {
     const int q_per_wg = WAVES * 32;
@@ -793,13 +806,8 @@ wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipSt
                                           wk::align_up((size_t)a.splits * a.H * a.N_q * WK_D * sizeof(float), 256));
     const int items = a.H * a.n_qtiles * a.splits * (a.n_chunks > 0 ? a.n_chunks : 1);
     a.per_xcd = (items + kXcds - 1) / kXcds;
-    static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
-    if (!lds_limit_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<WAVES>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
-            return WK_ERR_HIP;
-        lds_limit_set = true;
-    }
+    const wk_status lds_rc = allow_large_lds();
+    if (lds_rc != WK_OK) return lds_rc;
     if (a.O)
         hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
     else
@@ -870,9 +878,8 @@ wk_status launch_plain(AttnArgs a, int dtype, hipStream_t st) {
     } else {
         a.n_qtiles = (a.N_q + 255) / 256;
         a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
-            return WK_ERR_HIP;
+        const wk_status rc = allow_large_lds();
+        if (rc != WK_OK) return rc;
         hipLaunchKernelGGL(k_attn_bf16<8>, dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a);
     }
     WK_LAUNCH_CHECK();
