@@ -478,6 +478,18 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
     issue_tile(t0 + 2, (sh + 2) & 3);
     __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tiles 0 and 1 of this wave have landed
     __syncthreads();
+    if (qt * (WAVES * 32) + wave * 32 >= a.N_q) {
+        // A wave whose 32 queries all lie past N_q (last query tile of a head): it keeps loading its
+        // share of every tile and meets every barrier, but leaves the matrix and vector pipes of its
+        // SIMD to the wave that has work.
+        for (int j = 0; j < n_steps; ++j) {
+            issue_tile(t0 + j + 3, (j + sh + 3) & 3);
+            __builtin_amdgcn_s_waitcnt(0x0F74);
+            __syncthreads();
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        return;
+    }
     f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
     float mt;
     if (sh & 1) { compute_s(sh * kTileBytes, s_b); mt = tile_max(s_b); }
@@ -688,9 +700,11 @@ __global__ __launch_bounds__(512, 4) void k_lse_bf16(AttnArgs a) {
     };
     using P0 = std::integral_constant<int, 0>;
     using P2 = std::integral_constant<int, 2>;
+    const bool idle = qt * 256 + wave * 32 >= a.N_q;   // no valid query in this wave: loads and barriers only
     auto full_pair = [&](int j, auto pos_tag) {
         constexpr int POS = decltype(pos_tag)::value;
         open_pair(j, pos_tag);
+        if (idle) return;
         tile(POS * kTileBytes, j * kKeys, false);
         tile((POS + 1) * kTileBytes, (j + 1) * kKeys, false);
     };
@@ -698,6 +712,7 @@ __global__ __launch_bounds__(512, 4) void k_lse_bf16(AttnArgs a) {
     auto last_pair = [&](int j, auto pos_tag, int full) {
         constexpr int POS = decltype(pos_tag)::value;
         open_pair(j, pos_tag);
+        if (idle) return;
         if (full) {
             tile(POS * kTileBytes, j * kKeys, false);
             if (tail) tile((POS + 1) * kTileBytes, (j + 1) * kKeys, true);
