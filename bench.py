@@ -214,7 +214,13 @@ def main():
             lambda: wk.wk_compress_chunk(gdesc, evicted[0], evicted[1], evicted[2], ev_idx, ev_k, ev_v, gws), reps)
     row_bytes = cfg.d * Q.element_size()
     gather_bytes = 2 * 2 * cfg.H * cfg.R * n_out * row_bytes   # retrieved rows of K and V, read + write
+    # ceilings for the gather: a plain device-to-device copy of the same bytes (HBM store) ...
+    flat = Kw.view(-1)[: (gather_bytes // 2) // Kw.element_size()]
+    dst = torch.empty_like(flat)
+    t_d2d = time_call(lambda: dst.copy_(flat), reps)
+    del dst
     extra = {
+        "d2d_copy_ceiling_GBps": 2 * flat.numel() * flat.element_size() / (t_d2d * 1e-3) / 1e9,
         "attention_tflops": att_tflops,
         "pct_bf16_mfma_peak": 100.0 * att_tflops / PEAK_BF16_TFLOPS,
         "ms_per_chunk": per_call,
@@ -268,6 +274,12 @@ def main():
         t_pin = time_call(lambda: wk.wk_gather_window(pstore.desc, ids, n_found, cfg.R, None, None, cfg.n_native,
                                                       Kw, Vw, N_kv, n_win), 3)
         link_bytes = 2 * cfg.H * cfg.R * n_out * row_bytes
+        # ... and a plain pinned-host to device copy of as many bytes (pinned store)
+        n_link = link_bytes // pk.element_size()
+        dst = torch.empty(n_link, dtype=dt, device=dev)
+        t_h2d = time_call(lambda: dst.copy_(pk.view(-1)[:n_link], non_blocking=True), 3)
+        extra["h2d_copy_ceiling_GBps"] = link_bytes / (t_h2d * 1e-3) / 1e9
+        del dst
         extra["ms_per_chunk"]["gather_pinned_host"] = t_pin
         extra["gather_pinned_host_GBps"] = link_bytes / (t_pin * 1e-3) / 1e9
         extra["ms_per_step_pinned_store"] = ms_step - per_call["gather_hbm"] + t_pin
