@@ -15,8 +15,9 @@
  *   - "device" pointers must be readable/writable by kernels on the current
  *     HIP device (HBM, or host memory allocated pinned+mapped where stated).
  *     "host" pointers are ordinary host memory read during the call.
- *   - The caller owns every buffer.  The library allocates nothing, frees
- *     nothing and keeps no pointer after a call returns.
+ *   - The caller owns every buffer.  The library allocates no memory, frees
+ *     nothing and keeps no pointer after a call returns.  (wk_prefetch_create
+ *     is the one call that creates runtime objects: a stream and events.)
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns without waiting for it.
  *   - Argument errors are detected before anything is launched, leave all
@@ -190,7 +191,7 @@ typedef struct wk_store_desc {
  *              are already in place in the window and are not copied
  *   K_win,V_win device out, [H][win_capacity][d]; rows past the assembled length are untouched
  *   n_win      device out, int32 = n_native + sum of retrieved chunk lengths.  May be NULL.
- * Errors: INVALID_ARG, UNSUPPORTED (d != 128, R_max > 1024),
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, R_max > 1024, win_capacity >= 2^26 rows),
  *         SHAPE (win_capacity < n_native + R_max * max_tok). */
 wk_status wk_gather_window(const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids,
                            int32_t R_max, const void *K_native, const void *V_native,
