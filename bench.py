@@ -239,7 +239,7 @@ def main():
         hidden = sum(cfg.q_frames - 1 - f for f in range(cfg.q_frames)) * cfg.T * cfg.T
         bc_flops = flops - 4.0 * hidden * cfg.d * cfg.H
         extra["attention_block_causal"] = {"ms": t_bc, "tflops": bc_flops / (t_bc * 1e-3) / 1e12,
-                                           "launches": cfg.q_frames + 2}
+                                           "launches": 2}
         del bc_ws
 
     if cfg.M > 0 and cfg.M <= wk.WK_QUERY_MAX_CHUNKS:

@@ -84,6 +84,18 @@ __device__ inline bool work_item(const AttnArgs &a, int &c, int &h, int &qt, int
     return true;
 }
 
+// Several launches folded into one grid (used by the frame-causal entry point): each entry is what
+// one plain launch would have been told -- which queries, which key range, which partial slot.
+// Work items are numbered head-major over all entries, so a head's entries share an XCD.
+struct SubLaunch { int q_off, N_q, n_qtiles, kv_off, N_kv, kv_start, part_slot; };
+constexpr int kMaxSub = 8;
+struct SubTable { int n, per_head; SubLaunch s[kMaxSub]; };
+
+// MULTI: pick this workgroup's entry and make the (by-value) arguments look like that launch.
+template <bool MULTI>
+__device__ inline bool select_work(AttnArgs &a, const SubTable &t, size_t row_bytes, int &c, int &h, int &qt,
+                                   int &sp);
+
 // The window this workgroup reads: its keys, row stride between heads and length; where lse goes.
 struct Window {
     const char *K;
@@ -111,6 +123,33 @@ __device__ inline Window window_of(const AttnArgs &a, int c) {
     return w;
 }
 
+template <bool MULTI>
+__device__ inline bool select_work(AttnArgs &a, const SubTable &t, size_t row_bytes, int &c, int &h, int &qt,
+                                   int &sp) {
+    if constexpr (!MULTI) {
+        return work_item(a, c, h, qt, sp);
+    } else {
+        const int lin = blockIdx.x;
+        const int w = (lin % kXcds) * a.per_xcd + lin / kXcds;
+        if (lin / kXcds >= a.per_xcd || w >= a.H * t.per_head) return false;
+        h = w / t.per_head;
+        int r = w % t.per_head, e = 0;
+        while (e + 1 < t.n && r >= t.s[e].n_qtiles) {
+            r -= t.s[e].n_qtiles;
+            ++e;
+        }
+        qt = r;
+        c = 0;
+        sp = 0;
+        const SubLaunch u = t.s[e];
+        a.q_off = u.q_off; a.N_q = u.N_q; a.n_qtiles = u.n_qtiles;
+        a.N_kv = u.N_kv; a.kv_start = u.kv_start; a.part_slot = u.part_slot;
+        a.K += (size_t)u.kv_off * row_bytes;
+        a.V += (size_t)u.kv_off * row_bytes;
+        return true;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // fp32: v_mfma_f32_32x32x2_f32, 4 waves x 32 queries per workgroup, 32-key tiles.
 // ------------------------------------------------------------------------------------------
@@ -119,11 +158,12 @@ constexpr int kF32Keys = 32;
 constexpr int kF32KPitch = WK_D + 4;  // floats; 16 lanes x 16 B then cover all 64 banks
 constexpr int kF32VPitch = WK_D + 8;  // rows 4 apart land 32 banks apart
 
-__global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a) {
+template <bool MULTI>
+__global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a, SubTable sub) {
     __shared__ float Ks[kF32Keys * kF32KPitch];
     __shared__ float Vs[kF32Keys * kF32VPitch];
     int c, h, qt, sp;
-    if (!work_item(a, c, h, qt, sp)) return;
+    if (!select_work<MULTI>(a, sub, 512, c, h, qt, sp)) return;
     const Window win = window_of(a, c);
     const int n_kv = win.n_kv;
     float *const lse = win.lse;
@@ -284,12 +324,12 @@ __device__ inline float max_across_halves(float x) {
 #define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a) {
+template <int WAVES, bool MULTI>
+__global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTable sub) {
     static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
     extern __shared__ __attribute__((aligned(256))) char smem[];
     int c, h, qt, sp;
-    if (!work_item(a, c, h, qt, sp)) return;
+    if (!select_work<MULTI>(a, sub, 256, c, h, qt, sp)) return;
     const Window win = window_of(a, c);
     const int n_kv = win.n_kv;
     float *const lse = win.lse;
@@ -800,7 +840,9 @@ size_t split_workspace_bytes(int H, int N_q, int splits) {
 wk_status allow_large_lds() {
     static bool done = false;
     if (!done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
             return WK_ERR_HIP;
         done = true;
@@ -824,7 +866,8 @@ wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipSt
     const wk_status lds_rc = allow_large_lds();
     if (lds_rc != WK_OK) return lds_rc;
     if (a.O)
-        hipLaunchKernelGGL(k_attn_bf16<WAVES>, dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a);
+        hipLaunchKernelGGL((k_attn_bf16<WAVES, false>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a,
+                           SubTable{});
     else
         hipLaunchKernelGGL(k_lse_bf16, dim3(a.per_xcd * kXcds), dim3(512), kVRing, st, a);
     WK_LAUNCH_CHECK();
@@ -873,7 +916,7 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
         a.n_qtiles = (N_q + q_per_wg - 1) / q_per_wg;
         const int items = H * a.n_qtiles;
         a.per_xcd = (items + kXcds - 1) / kXcds;
-        hipLaunchKernelGGL(k_attn_f32, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a);
+        hipLaunchKernelGGL(k_attn_f32<false>, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a, SubTable{});
         WK_LAUNCH_CHECK();
         return WK_OK;
     }
@@ -889,13 +932,13 @@ wk_status launch_plain(AttnArgs a, int dtype, hipStream_t st) {
     if (dtype == WK_F32) {
         a.n_qtiles = (a.N_q + kF32Waves * 32 - 1) / (kF32Waves * 32);
         a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
-        hipLaunchKernelGGL(k_attn_f32, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a);
+        hipLaunchKernelGGL(k_attn_f32<false>, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a, SubTable{});
     } else {
         a.n_qtiles = (a.N_q + 255) / 256;
         a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
         const wk_status rc = allow_large_lds();
         if (rc != WK_OK) return rc;
-        hipLaunchKernelGGL(k_attn_bf16<8>, dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a);
+        hipLaunchKernelGGL((k_attn_bf16<8, false>), dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a, SubTable{});
     }
     WK_LAUNCH_CHECK();
     return WK_OK;
@@ -910,9 +953,11 @@ extern "C" size_t wk_attention_block_causal_workspace_bytes(int32_t H, int32_t N
 
 // Frame-level causal mask inside the chunk being denoised, as two key ranges per query frame
 // whose partial (O, max, sum) results k_attn_merge combines: range A = window rows up to and
-// including the query's own frame of the chunk (one launch per frame: all its queries share the
-// range), range B = the rows behind the chunk (one launch for all queries).  The kernels run
-// unchanged; they are only told which queries, which rows and which partial slot.
+// including the query's own frame of the chunk (all queries of a frame share it), range B = the
+// rows behind the chunk (shared by all queries).  The attention loop runs unchanged; a workgroup is
+// only told which queries, which rows and which partial slot are its own -- through a table of up
+// to 8 such (queries, rows, slot) entries served by one grid, or, for more frames than that, by
+// one launch per entry.
 extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win, const void *V_win, void *O,
                                                float *lse, int32_t H, int32_t N_q, int32_t N_kv, int32_t d,
                                                int32_t kv_row_stride, int32_t dtype, float scale,
@@ -948,24 +993,53 @@ extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win,
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
 
-    AttnArgs b = a;   // the rows behind the chunk, every query
-    const int start = denoise_row0 + N_q;
-    b.K += (size_t)start * row_bytes;
-    b.V += (size_t)start * row_bytes;
-    b.N_kv = N_kv - start;
-    b.kv_start = start;
-    b.part_slot = 1;
-    wk_status rc = launch_plain(b, dtype, st);
-    if (rc != WK_OK) return rc;
     const int frames = N_q / frame_T;
-    for (int f = 0; f < frames; ++f) {   // rows up to the end of frame f of the chunk, that frame's queries
-        AttnArgs p = a;
-        p.N_q = frame_T;
-        p.q_off = f * frame_T;
-        p.N_kv = denoise_row0 + (f + 1) * frame_T;
-        p.part_slot = 0;
-        rc = launch_plain(p, dtype, st);
+    const int start = denoise_row0 + N_q;
+    if (frames + 1 <= kMaxSub) {
+        // all ranges in one grid: entry 0 = the rows behind the chunk for every query (the long
+        // items first), entries 1.. = the prefix up to frame f for that frame's queries
+        const int q_per_wg = dtype == WK_F32 ? kF32Waves * 32 : 256;
+        SubTable t;
+        t.n = frames + 1;
+        t.s[0] = SubLaunch{0, N_q, (N_q + q_per_wg - 1) / q_per_wg, start, N_kv - start, start, 1};
+        t.per_head = t.s[0].n_qtiles;
+        for (int f = 0; f < frames; ++f) {
+            t.s[f + 1] = SubLaunch{f * frame_T, frame_T, (frame_T + q_per_wg - 1) / q_per_wg, 0,
+                                   denoise_row0 + (f + 1) * frame_T, 0, 0};
+            t.per_head += t.s[f + 1].n_qtiles;
+        }
+        for (int e = t.n; e < kMaxSub; ++e) t.s[e] = SubLaunch{0, 0, 0, 0, 0, 0, 0};
+        AttnArgs g = a;
+        if ((long long)H * t.per_head + kXcds > 0x7fffffffLL) return WK_ERR_UNSUPPORTED;
+        g.per_xcd = (H * t.per_head + kXcds - 1) / kXcds;
+        g.n_qtiles = 0;
+        if (dtype == WK_F32) {
+            hipLaunchKernelGGL(k_attn_f32<true>, dim3(g.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, g, t);
+        } else {
+            const wk_status lrc = allow_large_lds();
+            if (lrc != WK_OK) return lrc;
+            hipLaunchKernelGGL((k_attn_bf16<8, true>), dim3(g.per_xcd * kXcds), dim3(512), kSmemBytes, st, g, t);
+        }
+        WK_LAUNCH_CHECK();
+    } else {
+        // more frames than the table holds: the same ranges as separate launches
+        AttnArgs b = a;   // the rows behind the chunk, every query
+        b.K += (size_t)start * row_bytes;
+        b.V += (size_t)start * row_bytes;
+        b.N_kv = N_kv - start;
+        b.kv_start = start;
+        b.part_slot = 1;
+        wk_status rc = launch_plain(b, dtype, st);
         if (rc != WK_OK) return rc;
+        for (int f = 0; f < frames; ++f) {   // rows up to the end of frame f of the chunk, that frame's queries
+            AttnArgs p = a;
+            p.N_q = frame_T;
+            p.q_off = f * frame_T;
+            p.N_kv = denoise_row0 + (f + 1) * frame_T;
+            p.part_slot = 0;
+            rc = launch_plain(p, dtype, st);
+            if (rc != WK_OK) return rc;
+        }
     }
     AttnArgs m = a;
     m.splits = 2;
@@ -1010,7 +1084,7 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
     if (store->dtype == WK_F32) {
         a.n_qtiles = (N_q + q_per_wg - 1) / q_per_wg;
         a.per_xcd = (int)((items + kXcds - 1) / kXcds);
-        hipLaunchKernelGGL(k_attn_f32, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a);
+        hipLaunchKernelGGL(k_attn_f32<false>, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a, SubTable{});
         WK_LAUNCH_CHECK();
         return WK_OK;
     }

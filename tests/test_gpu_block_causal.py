@@ -90,3 +90,14 @@ def test_block_causal_config2_size_sampled_rows():
     mx = _check(Q, O[:, sel], lse[:, sel], ref, ref_lse)
     print(f"block-causal config-2 size: max-abs {mx:.2e} on {rows.size} rows x {cfg.H} heads")
     assert torch.isfinite(O.float()).all()
+
+
+def test_block_causal_many_frames_uses_separate_launches():
+    """More frames than the one-grid table holds (9 > 7): the per-range launches give the same answer."""
+    cfg = ws.get_config(1).with_(H=2)
+    T, F, row0 = 40, 9, 100
+    Q = ws.make_queries(cfg, "cpu", T * F)
+    K, V = ws.make_native(cfg, "cpu", row0 + T * F + 150)
+    O, lse = _run(Q, K, V, row0, T)
+    ref, ref_lse = oracle.attention_block_causal(Q, K, V, row0, T, want_lse=True)
+    _check(Q, O, lse, ref, ref_lse)
