@@ -22,9 +22,10 @@ import paper_2605_22718_amd as wk
 import wk_synth as ws
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
-# HBM bytes per wk_attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs),
-# per workload index; see profiles/hbm_traffic_lingbot_pmc.txt for the commands and the calibration
-MEASURED_ATTENTION_TRAFFIC = {2: (418970 + 51360) * 1024}
+# HBM bytes per wk_attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
+# scaled by what the counter reads for the plain calibration copy (0.500 and 1.000), per workload index;
+# see profiles/hbm_traffic_lingbot_pmc.txt for the commands
+MEASURED_ATTENTION_TRAFFIC = {2: (2 * 667783 + 46800) * 1024}
 
 
 def parse():
@@ -219,6 +220,12 @@ def main():
     dst = torch.empty_like(flat)
     t_d2d = time_call(lambda: dst.copy_(flat), reps)
     del dst
+    # a plain copy of a window-sized buffer that is cold in the caches: the copy of known size against which
+    # the rocprofv3 FETCH_SIZE / WRITE_SIZE readings of the library's kernels are calibrated (k_copy_plain)
+    cal_src = Kw.clone()
+    cal_dst = torch.zeros_like(Kw)          # written after cal_src: pushes it out of the Infinity Cache
+    wk.wk_calibration_copy(cal_dst, cal_src)
+    del cal_src, cal_dst
     extra = {
         "d2d_copy_ceiling_GBps": 2 * flat.numel() * flat.element_size() / (t_d2d * 1e-3) / 1e9,
         "attention_tflops": att_tflops,

@@ -367,6 +367,12 @@ wk_status wk_prefetch_acquire(wk_prefetch *p, int32_t slot, void *hip_stream);
  * into the slot waits for them. */
 wk_status wk_prefetch_release(wk_prefetch *p, int32_t slot, void *hip_stream);
 
+/* Measurement aid, not a step of the method: a straight device copy of `bytes` bytes (a multiple of
+ * 16, both pointers 16-byte aligned, ranges must not overlap) with ordinary cached 16-byte loads and
+ * stores.  Profilers' HBM byte counters are calibrated against it: it moves a known number of bytes
+ * with the access pattern of the attention kernels' tile loads.  Errors: INVALID_ARG. */
+wk_status wk_calibration_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
 /* Device-visible address of a pinned+mapped host allocation (for K_ptr/V_ptr tables and for
  * K_out/V_out of wk_compress_chunk).  Errors: INVALID_ARG, HIP (memory is not pinned). */
 wk_status wk_host_device_pointer(void *host_ptr, void **device_ptr);

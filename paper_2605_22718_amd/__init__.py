@@ -32,7 +32,7 @@ EXPORTS = [
     "wk_prefetch_create", "wk_prefetch_destroy", "wk_prefetch_stream", "wk_prefetch_after", "wk_prefetch_gather",
     "wk_prefetch_acquire", "wk_prefetch_release",
     "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_attention_workspace_bytes",
-    "wk_host_device_pointer",
+    "wk_host_device_pointer", "wk_calibration_copy",
     "wk_status_string",
 ]
 
@@ -127,6 +127,8 @@ def lib():
         L.wk_attention_block_causal_workspace_bytes.argtypes = [i32, i32]
         L.wk_attention_workspace_bytes.restype = C.c_size_t
         L.wk_attention_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.wk_calibration_copy.restype = C.c_int
+        L.wk_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.wk_host_device_pointer.restype = C.c_int
         L.wk_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
         L.wk_status_string.restype = C.c_char_p
@@ -359,6 +361,13 @@ def wk_prefetch_acquire(p, slot, stream=None):
 
 def wk_prefetch_release(p, slot, stream=None):
     _check(lib().wk_prefetch_release(p, slot, _stream() if stream is None else stream), "wk_prefetch_release")
+
+
+def wk_calibration_copy(dst, src):
+    """wk_calibration_copy: plain device copy of src into dst (same byte size)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(lib().wk_calibration_copy(_dev(dst, "dst"), _dev(src, "src"), n, _stream()), "wk_calibration_copy")
 
 
 def wk_attention_workspace_bytes(H, N_q, N_kv, dtype) -> int:

@@ -192,6 +192,45 @@ extern "C" wk_status wk_gather_window(const wk_store_desc *store, const int32_t 
                              n_win, 0, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
+namespace {
+
+// Straight copy with ordinary (cached) 16-byte loads and stores, one vector per lane and pass: the
+// access pattern of the tile loads in the attention kernels, with a byte count known exactly.
+__global__ __launch_bounds__(kThreads) void k_copy_plain(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                         long long n_vec) {
+    const long long per_block = (long long)kThreads * kVecPerThread;
+    for (long long base = (long long)blockIdx.x * per_block; base < n_vec; base += (long long)gridDim.x * per_block) {
+        uint4 buf[kVecPerThread];
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            const long long v = base + threadIdx.x + (long long)i * kThreads;
+            if (v < n_vec) buf[i] = src[v];
+        }
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            const long long v = base + threadIdx.x + (long long)i * kThreads;
+            if (v < n_vec) dst[v] = buf[i];
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" wk_status wk_calibration_copy(void *dst, const void *src, size_t bytes, void *hip_stream) {
+    if (!dst || !src || bytes % 16 != 0) return WK_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
+        return WK_ERR_INVALID_ARG;
+    if (bytes == 0) return WK_OK;
+    const long long n_vec = (long long)(bytes / 16);
+    long long grid = (n_vec + kVecPerBlock - 1) / kVecPerBlock;
+    if (grid > 0x7fffffffLL) grid = 0x7fffffffLL;
+    hipLaunchKernelGGL(k_copy_plain, dim3((unsigned)grid), dim3(kThreads), 0,
+                       reinterpret_cast<hipStream_t>(hip_stream), reinterpret_cast<const uint4 *>(src),
+                       reinterpret_cast<uint4 *>(dst), n_vec);
+    WK_LAUNCH_CHECK();
+    return WK_OK;
+}
+
 extern "C" wk_status wk_host_device_pointer(void *host_ptr, void **device_ptr) {
     if (!host_ptr || !device_ptr) return WK_ERR_INVALID_ARG;
     void *dp = nullptr;

@@ -98,3 +98,14 @@ def test_config1_sized_gather():
     oK, oV, _ = oracle.gather([k[:1].cpu() for k, _ in ks], [v[:1].cpu() for _, v in ks], [4, 0, 5, 2],
                               Kn[:1].cpu(), Vn[:1].cpu(), cap)
     assert torch.equal(bits(Kw[:1].cpu()), bits(oK)) and torch.equal(bits(Vw[:1].cpu()), bits(oV))
+
+
+def test_calibration_copy_is_exact():
+    d = dev()
+    g = torch.Generator(device="cpu").manual_seed(1)
+    for n in (16, 48, 32 * 1024 + 16, 5 * 1024 * 1024 + 32):
+        src = torch.randint(0, 255, (n,), dtype=torch.uint8, generator=g).to(d)
+        dst = torch.zeros(n + 16, dtype=torch.uint8, device=d)
+        wk.wk_calibration_copy(dst[:n], src)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0

@@ -164,6 +164,11 @@ def test_argument_validation_of_the_other_calls():
     assert bc(ws=None) == wk.WK_ERR_WORKSPACE
     assert bc(ws_bytes=100) == wk.WK_ERR_WORKSPACE
     assert wk.wk_attention_block_causal_workspace_bytes(2, 6) >= 2 * 2 * 6 * (128 + 2) * 4
+    # calibration copy
+    assert L.wk_calibration_copy(None, one, 32, None) == wk.WK_ERR_INVALID_ARG
+    assert L.wk_calibration_copy(one, one, 24, None) == wk.WK_ERR_INVALID_ARG           # not a multiple of 16
+    assert L.wk_calibration_copy(C.c_void_p(264), one, 32, None) == wk.WK_ERR_INVALID_ARG  # misaligned
+    assert L.wk_calibration_copy(one, one, 0, None) == wk.WK_OK
     # key-range splits are only proposed when the plain grid would leave compute units idle
     assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
     assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4
