@@ -33,7 +33,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload index (1 Matrix-Game, 2 LingBot)")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2],
+                    help="workload index: 2 = LingBot-shaped (the workload the metric is quoted on), "
+                         "1 = Matrix-Game-shaped; the other configurations are parity-test cases")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pinned", action="store_true", help="skip the pinned-host store measurement")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
