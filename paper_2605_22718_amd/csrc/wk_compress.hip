@@ -145,98 +145,143 @@ __global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__
 // candidate rows 8*(r/4) + 4*(l/32) + r%4, so the column scale is a per-lane scalar.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-constexpr int kGemmTile = 64;
-constexpr int kGemmMaxSplits = 8;   // anchor tiles of one candidate tile may be split over this many workgroups
+// ---- Eq. 5 as the similarity GEMM on the matrix cores (WK_SCORE_GEMM) ------------------------
+//
+// C[i][j] = sum over the group's heads and the 128 features of (anchor key i) . (candidate key j),
+// then partial[j] = sum_i C[i][j] / |k_i|.  A workgroup of 8 waves owns a 256 (anchors) x 256
+// (candidates) block of C: wave (wa, wc) holds 128 x 64 of it in eight 32x32 accumulators, so a
+// 16-feature step costs 4 + 2 operand reads from LDS for 8 MFMAs.  The contraction runs over
+// heads x 128 features in steps of 64 features; both operand tiles of a step (256 rows x 128 bytes
+// each) go from global memory straight into one of two LDS stages (global_load_lds), the next step's
+// loads being in flight while the current one is multiplied.  Rows are 128 bytes, their eight
+// 16-byte chunks stored at chunk ^ ((row >> 1) & 7), which makes the 16 lanes of an operand read
+// hit 16 different bank groups.  The block of C never leaves registers: it is folded with the
+// column weights 1/|k_i| and summed over the anchors in the epilogue.
+constexpr int kGemmTile = 256;        // anchors and candidates per workgroup block
+constexpr int kGemmMaxSplits = 32;    // partial sums per candidate: (anchor blocks) x (head ranges), one workgroup each
+constexpr int kGemmStage = 2 * kGemmTile * 128;   // bytes: anchor tile + candidate tile of one 64-feature step
+constexpr int kGemmLds = 2 * kGemmStage + kGemmTile * 4 + 2 * kGemmTile * 4;
 
-// partial[((b*G+g)*splits + sp)*n_cand + j] = sum over the anchors of split sp of (k_j . k_i) / |k_i|
-__global__ __launch_bounds__(256) void k_score_gemm(const char *__restrict__ K, const char *__restrict__ A,
-                                                    CompressDims p, const double *__restrict__ nsq_a,
-                                                    int splits, float *__restrict__ partial) {
-    __shared__ __attribute__((aligned(16))) char At[kGemmTile * 256];   // candidate rows of one head, chunk c at c ^ (row & 15)
-    __shared__ __attribute__((aligned(16))) char Bt[kGemmTile * 256];   // anchor rows of one head
-    __shared__ float part[2][kGemmTile];
+#define WK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define WK_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+// partial[((b*G+g)*splits + sp)*n_cand + j], splits = asplits*hsplits, sp = sh*asplits + sa: the sum over the
+// anchors of blocks sa, sa+asplits, ... and over the heads of range sh of (k_j . k_i)_heads / |k_i|.  (The sum
+// over heads commutes with the weighting, so head ranges are just more partial sums for the finish kernel;
+// they fill the chip when one chunk alone gives too few blocks.)
+__global__ __launch_bounds__(512, 2) void k_score_gemm(const char *__restrict__ K, const char *__restrict__ A,
+                                                       CompressDims p, const double *__restrict__ nsq_a,
+                                                       int asplits, int hsplits, float *__restrict__ partial) {
+    extern __shared__ __attribute__((aligned(256))) char smem[];
+    float *w_lds = reinterpret_cast<float *>(smem + 2 * kGemmStage);   // [256] column weights of the anchor block
+    float *red = w_lds + kGemmTile;                                    // [2][256] partial sums of the two anchor halves
+    const int splits = asplits * hsplits;
     const int g = blockIdx.y / splits, sp = blockIdx.y % splits, b = blockIdx.z;
+    const int sa = sp % asplits, sh = sp / asplits;
     const int j0 = blockIdx.x * kGemmTile;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, gh = lane >> 5;
-    const int cs = wave & 1, as = wave >> 1;
+    const int wa = wave & 1, wc = wave >> 1;
     const double *na = nsq_a + ((size_t)b * p.G + g) * p.T;
-    const int n_at = (p.T + kGemmTile - 1) / kGemmTile;
-    const int per = (n_at + splits - 1) / splits;
-    const int at_begin = sp * per, at_end = min(n_at, at_begin + per);
-    float sum[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sum[r] = 0.f;
+    const int n_ablocks = (p.T + kGemmTile - 1) / kGemmTile;
+    const int h_per = (p.hg + hsplits - 1) / hsplits;
+    const int h_lo = sh * h_per, h_hi = min(p.hg, h_lo + h_per);
+    const int n_steps = max(h_hi - h_lo, 0) * 2;   // 64-feature steps of the contraction
 
-    // one iteration = (anchor tile, head); the next iteration's tiles are fetched into registers
-    // while the matrix cores work on the current ones
-    const int n_iter = (at_end - at_begin) * p.hg;
-    uint4 ra[4], rb[4];
-    auto fetch = [&](int it) {
-        const int at = at_begin + it / p.hg, hh = it % p.hg;
-        const int h = p.G == 1 ? hh : g;
-        const char *Kh = K + ((size_t)b * p.H + h) * p.n_tok * 256;
-        const char *Ah = A + ((size_t)b * p.H + h) * p.a_rows * 256;
+    // operand reads: chunk 2*st + gh of row (128*wa + 32*mb + col) resp. (64*wc + 32*nb + col)
+    const char *a_rd[4], *b_rd[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int x = tid + i * 256;
-            const int row = x >> 4, c = x & 15;
-            const int cj = min(j0 + row, p.n_cand - 1), ai = min(at * kGemmTile + row, p.T - 1);   // clamped rows are masked later
-            ra[i] = *reinterpret_cast<const uint4 *>(Kh + (size_t)(p.first_cand + cj) * 256 + c * 16);
-            rb[i] = *reinterpret_cast<const uint4 *>(Ah + (size_t)ai * 256 + c * 16);
-        }
-    };
-    if (n_iter > 0) fetch(0);
-    f32x16 D;
+    for (int st = 0; st < 4; ++st) {
+        const int slot = ((2 * st + gh) ^ ((col >> 1) & 7)) << 4;
+        a_rd[st] = smem + (128 * wa + col) * 128 + slot;
+        b_rd[st] = smem + kGemmTile * 128 + (64 * wc + col) * 128 + slot;
+    }
+    // tile loads: thread t fills 16-byte slot (t & 7) of rows 64*i + (t >> 3), i = 0..3, of both tiles
+    const int ld_row = tid >> 3;
+    const unsigned ld_chunk = (unsigned)(((tid & 7) ^ ((tid >> 4) & 7)) << 4);
+    unsigned cand_off[4];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) D[r] = 0.f;
-    for (int it = 0; it < n_iter; ++it) {
-        __syncthreads();   // previous tiles fully consumed
+    for (int i = 0; i < 4; ++i)   // rows past the last candidate are clamped; their sums are never written
+        cand_off[i] = (unsigned)(p.first_cand + min(j0 + 64 * i + ld_row, p.n_cand - 1)) * 256u + ld_chunk;
+    char *const dma_dst = smem + wave * 1024;
+
+    float psum[2] = {0.f, 0.f};
+    for (int ab = sa; ab < n_ablocks; ab += asplits) {
+        unsigned anc_off[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int x = tid + i * 256;
-            const int row = x >> 4, c = x & 15;
-            *reinterpret_cast<uint4 *>(At + row * 256 + ((c ^ (row & 15)) << 4)) = ra[i];
-            *reinterpret_cast<uint4 *>(Bt + row * 256 + ((c ^ (row & 15)) << 4)) = rb[i];
-        }
-        __syncthreads();
-        if (it + 1 < n_iter) fetch(it + 1);
-        const int rowa = 32 * cs + col, rowb = 32 * as + col;
+        for (int i = 0; i < 4; ++i)   // anchors past T are clamped and get weight 0
+            anc_off[i] = (unsigned)min(ab * kGemmTile + 64 * i + ld_row, p.T - 1) * 256u + ld_chunk;
+        auto issue = [&](int step, int stage) {
+            const int hh = h_lo + (step >> 1);
+            const int h = p.G == 1 ? hh : g;
+            const char *Ah = A + ((size_t)b * p.H + h) * p.a_rows * 256 + (step & 1) * 128;
+            const char *Kh = K + ((size_t)b * p.H + h) * p.n_tok * 256 + (step & 1) * 128;
+            char *dst = dma_dst + stage * kGemmStage;
 #pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(At + rowa * 256 + (((2 * st + gh) ^ (rowa & 15)) << 4));
-            const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(Bt + rowb * 256 + (((2 * st + gh) ^ (rowb & 15)) << 4));
-            D = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, kb, D, 0, 0, 0);
-        }
-        if (it % p.hg == p.hg - 1) {   // all heads of the group accumulated: fold this anchor tile in
-            const int i = (at_begin + it / p.hg) * kGemmTile + 32 * as + col;
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_global_load_lds(WK_GLB_PTR(Ah + anc_off[i]), WK_LDS_PTR(dst + i * 8192), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(WK_GLB_PTR(Kh + cand_off[i]), WK_LDS_PTR(dst + kGemmTile * 128 + i * 8192),
+                                                 16, 0, 0);
+            }
+        };
+        __syncthreads();   // the previous block's weights and stages are no longer read
+        if (tid < kGemmTile) {
+            const int i = ab * kGemmTile + tid;
             float rn = 0.f;   // anchors past T (clamped duplicates) and zero-norm anchors contribute nothing
             if (i < p.T) {
                 const double n2 = na[i];
                 rn = n2 < 1e-60 ? 0.f : (float)(1.0 / sqrt(n2));
             }
+            w_lds[tid] = rn;
+        }
+        f32x16 acc[4][2];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sum[r] = fmaf(D[r], rn, sum[r]);
-                D[r] = 0.f;
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+        if (n_steps > 0) issue(0, 0);
+        for (int step = 0; step < n_steps; ++step) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the step's tiles has landed
+            __syncthreads();                      // everyone's has, and the other stage is free again
+            if (step + 1 < n_steps) issue(step + 1, (step + 1) & 1);
+            const int off = (step & 1) * kGemmStage;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                bf16x8 fa[4], fb[2];
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) fa[mb] = *reinterpret_cast<const bf16x8 *>(a_rd[st] + off + mb * 4096);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) fb[nb] = *reinterpret_cast<const bf16x8 *>(b_rd[st] + off + nb * 4096);
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[nb], acc[mb][nb], 0, 0, 0);
             }
         }
+        // fold the block in: accumulator register r of block mb is anchor 128*wa + 32*mb + 8*(r/4) + 4*gh + r%4
+        // (an empty head range has passed no barrier since the weights were written, and has nothing to add)
+        if (n_steps > 0)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float w = w_lds[128 * wa + 32 * mb + 8 * (r >> 2) + 4 * gh + (r & 3)];
+                psum[0] = fmaf(acc[mb][0][r], w, psum[0]);
+                psum[1] = fmaf(acc[mb][1][r], w, psum[1]);
+            }
     }
-    // sum over the 32 anchor columns held by the lanes of each half-wave
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float v = sum[r];
-#pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-        sum[r] = v;
-    }
-    if (col == 0) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) part[as][32 * cs + 8 * (r >> 2) + 4 * gh + (r & 3)] = sum[r];
+    for (int nb = 0; nb < 2; ++nb) {
+        const float v = psum[nb] + __shfl_xor(psum[nb], 32);
+        if (gh == 0) red[wa * kGemmTile + 64 * wc + 32 * nb + col] = v;
     }
     __syncthreads();
     if (tid < kGemmTile && j0 + tid < p.n_cand)
-        partial[(((size_t)b * p.G + g) * splits + sp) * p.n_cand + j0 + tid] = part[0][tid] + part[1][tid];
+        partial[(((size_t)b * p.G + g) * splits + sp) * p.n_cand + j0 + tid] = red[tid] + red[kGemmTile + tid];
 }
 
 // scores[(b*G+g)*n_cand + j] = (sum of the splits' partial sums) / (|k_j| T)
@@ -474,15 +519,28 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
                 hipLaunchKernelGGL(k_rows_normsq<DT>, g2, dim3(256), 0, st, Kc, p, p.n_tok, p.first_cand, p.n_cand,
                                    nsq_cand);
                 WK_LAUNCH_CHECK();
-                // enough workgroups for 256 CUs: split the anchor tiles of a candidate tile if need be
+                // one workgroup per (candidate block, anchor block); beyond 8 anchor blocks a workgroup
+                // walks several
                 const int cand_tiles = (p.n_cand + kGemmTile - 1) / kGemmTile;
-                const int n_at = (p.T + kGemmTile - 1) / kGemmTile;
-                int splits = (512 + cand_tiles * p.G * d->batch - 1) / (cand_tiles * p.G * d->batch);
-                splits = splits < 1 ? 1 : (splits > kGemmMaxSplits ? kGemmMaxSplits : splits);
-                splits = splits > n_at ? n_at : splits;
+                const int n_ablocks = (p.T + kGemmTile - 1) / kGemmTile;
+                const int asplits = n_ablocks < 8 ? n_ablocks : 8;
+                // head ranges: as many as keep the grid within one round of 256 workgroups
+                const long long blocks = (long long)cand_tiles * p.G * asplits * d->batch;
+                int hsplits = (int)(256 / (blocks > 0 ? blocks : 1));
+                hsplits = hsplits < 1 ? 1 : hsplits;
+                hsplits = hsplits > p.hg ? p.hg : hsplits;
+                hsplits = hsplits > kGemmMaxSplits / asplits ? kGemmMaxSplits / asplits : hsplits;
+                const int splits = asplits * hsplits;
                 float *partial = reinterpret_cast<float *>(wsp + ws.gemm_partial);
-                hipLaunchKernelGGL(k_score_gemm, dim3(cand_tiles, p.G * splits, d->batch), dim3(256), 0, st, Kc, A, p,
-                                   nsq, splits, partial);
+                static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
+                if (!lds_limit_set) {
+                    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_gemm),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds) != hipSuccess)
+                        return WK_ERR_HIP;
+                    lds_limit_set = true;
+                }
+                hipLaunchKernelGGL(k_score_gemm, dim3(cand_tiles, p.G * splits, d->batch), dim3(512), kGemmLds, st, Kc,
+                                   A, p, nsq, asplits, hsplits, partial);
                 WK_LAUNCH_CHECK();
                 hipLaunchKernelGGL(k_score_gemm_finish, dim3((p.n_cand + 255) / 256, d->batch * p.G), dim3(256), 0, st,
                                    partial, p, splits, nsq_cand, scores);
