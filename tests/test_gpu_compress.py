@@ -136,11 +136,9 @@ def test_gemm_scoring_external_anchor_batch_and_fp32_refusal():
     assert wk.wk_compress_workspace_bytes(desc) == 0      # the matrix-core variant is bf16 only
 
 
-@pytest.mark.parametrize("algo", [wk.WK_SCORE_FACTORED, wk.WK_SCORE_GEMM])
-@pytest.mark.parametrize("ci", [0, 1])
+# (config 0 is fp32; the matrix-core scoring variant is bf16 only)
+@pytest.mark.parametrize("ci,algo", [(0, wk.WK_SCORE_FACTORED), (1, wk.WK_SCORE_FACTORED), (1, wk.WK_SCORE_GEMM)])
 def test_config_sized_chunk_full_compare(ci, algo):
-    if ci == 0 and algo == wk.WK_SCORE_GEMM:
-        pytest.skip("config 0 is fp32; the matrix-core scoring variant is bf16 only")
     cfg = ws.get_config(ci)
     K, V, A = ws.make_chunk(cfg, 1)
     gi, gK, gV, gs, n_out = _gpu_compress(cfg, K, V, A, score_algo=algo)
