@@ -297,7 +297,8 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a, SubTabl
 // bf16: v_mfma_f32_32x32x16_bf16, 8 waves x 32 queries per workgroup, 64-key tiles.
 //
 // K and V tiles go from global memory straight into a 4-deep LDS ring (global_load_lds, no
-// register staging), three tiles ahead of their use.  Both tiles are row-major with their
+// register staging), K tiles four and V tiles three ahead of the step that loads them, which
+// gives each three steps to land (S^T is formed one step early, so K leads V by one tile).  Both tiles are row-major with their
 // 16-byte chunks permuted inside a row; the permutation is applied on the source side (each
 // lane fetches the chunk that belongs in its linear LDS slot).  K^ operands are plain 16-byte
 // reads; V^T operands are LDS transpose reads (ds_read_b64_tr_b16) of the row-major V tile.
@@ -408,24 +409,35 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     const unsigned last_off = (unsigned)(n_kv - 1) * 256u;
     char *const dma_dst = smem + wave * 2048;   // + slot*16384 (+ kVRing) + i*1024
 
-    // 4 loads per wave and tile.  Tiles that end past the window clamp their rows to the last one;
-    // those keys are masked (weight exactly 0) before they can contribute.
-    auto issue_tile = [&](int t, int slot) {
-        const unsigned t_off = (unsigned)t * (kKeys * 256u);
+    // Loads: 2 per wave for a K tile, 2 for a V tile (rel = tile index relative to t0).  Rows past the
+    // window clamp to the last key; those keys are masked (weight exactly 0) before they can contribute.
+    auto issue_k = [&](int rel, int slot) {
+        const unsigned t_off = (unsigned)(t0 + rel) * (kKeys * 256u);
         char *dst = dma_dst + slot * kTileBytes;
-        if ((t + 1) * kKeys <= n_kv) {
+        if ((t0 + rel + 1) * kKeys <= n_kv) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2; ++i)
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + (t_off + k_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
-            }
         } else {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const unsigned ko = min(t_off + k_src[i], last_off + (k_src[i] & 255u));
-                const unsigned vo = min(t_off + v_src[i], last_off + (v_src[i] & 255u));
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + ko), WK_LDS(dst + i * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + kVRing + i * 1024), 16, 0, 0);
+            }
+        }
+    };
+    auto issue_v = [&](int rel, int slot) {
+        const unsigned t_off = (unsigned)(t0 + rel) * (kKeys * 256u);
+        char *dst = dma_dst + slot * kTileBytes + kVRing;
+        if ((t0 + rel + 1) * kKeys <= n_kv) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const unsigned vo = min(t_off + v_src[i], last_off + (v_src[i] & 255u));
+                __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + i * 1024), 16, 0, 0);
             }
         }
     };
@@ -513,18 +525,27 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     // the 4-step unrolled loop below is entered at position sh and always ends on a full group.
     const int n_steps = t1 - t0 - 1;
     const int sh = (4 - (n_steps & 3)) & 3;
-    issue_tile(t0, sh);
-    issue_tile(t0 + 1, (sh + 1) & 3);
-    issue_tile(t0 + 2, (sh + 2) & 3);
-    __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): tiles 0 and 1 of this wave have landed
+    // Step j multiplies K tile j+1 (S^T one step early) and V tile j, so K runs one tile ahead of V:
+    // step j loads K tile j+4 into the slot of K tile j (read in step j-1) and V tile j+3 into the slot
+    // of V tile j-1.  Both then have three steps to land before the step that needs them.
+    issue_k(0, sh);
+    issue_k(1, (sh + 1) & 3);
+    issue_v(0, sh);
+    issue_k(2, (sh + 2) & 3);
+    issue_v(1, (sh + 1) & 3);
+    issue_k(3, (sh + 3) & 3);
+    issue_v(2, (sh + 2) & 3);
+    __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): K tiles 0, 1 and V tile 0 of this wave have landed
     __syncthreads();
     if (qt * (WAVES * 32) + wave * 32 >= a.N_q) {
         // A wave whose 32 queries all lie past N_q (last query tile of a head): it keeps loading its
         // share of every tile and meets every barrier, but leaves the matrix and vector pipes of its
         // SIMD to the wave that has work.
+        __syncthreads();   // the others' first S^T has been formed from K tile 0
         for (int j = 0; j < n_steps; ++j) {
-            issue_tile(t0 + j + 3, (j + sh + 3) & 3);
-            __builtin_amdgcn_s_waitcnt(0x0F74);
+            issue_k(j + 4, (j + sh) & 3);
+            issue_v(j + 3, (j + sh + 3) & 3);
+            __builtin_amdgcn_s_waitcnt(0x0F78);
             __syncthreads();
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -534,18 +555,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     float mt;
     if (sh & 1) { compute_s(sh * kTileBytes, s_b); mt = tile_max(s_b); }
     else        { compute_s(sh * kTileBytes, s_a); mt = tile_max(s_a); }
+    __syncthreads();   // K tile 0 has been read by every wave: step 0 may load K tile 4 into its slot
 
     // one pipeline step: tile j (ring position POS) is consumed, S^T of tile j+1 produced
     auto step = [&](int j, auto pos_tag, f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) {
         constexpr int POS = decltype(pos_tag)::value;
-        issue_tile(t0 + j + 3, (POS + 3) & 3);
+        issue_k(j + 4, POS);
+        issue_v(j + 3, (POS + 3) & 3);
         maybe_rescale(mt);
         compute_s(((POS + 1) & 3) * kTileBytes, s_next);
         bf16x8 pb[4];
         probabilities(s_cur, pb);
         accumulate_pv(POS * kTileBytes, pb);
         mt = tile_max(s_next);
-        __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): everything but tile j+3 has landed
+        __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): all but the loads of this step and the one before have landed
         __syncthreads();
     };
     using P0 = std::integral_constant<int, 0>;
