@@ -47,7 +47,7 @@ typedef enum {
 
 typedef enum { WK_F32 = 0, WK_BF16 = 1 } wk_dtype;
 
-/* Eq. 5 speaks of "key vectors at a given layer" and never of heads.
+/* Eq. 5 is written for the key vectors of a layer and never mentions heads.
  * SHARED: the key vector of a token is the concatenation of its H head slices and one
  *         index set serves the whole layer (the literal reading; default).
  * INDEPENDENT: Eq. 5 is applied per head (d = 128) and every head keeps its own,
@@ -70,7 +70,7 @@ typedef enum { WK_RATIO_CHUNK = 0, WK_RATIO_NONANCHOR = 1 } wk_ratio_kind;
  *         tile epilogue; the T x (F-1)T matrix is never written.  bf16 only. */
 typedef enum { WK_SCORE_FACTORED = 0, WK_SCORE_GEMM = 1 } wk_score_algo;
 
-/* How each distance term is "normalized across the retrieval candidate set" (Sec. 5.1). */
+/* How each distance term is normalised over the set of retrieval candidates (Sec. 5.1). */
 typedef enum { WK_NORM_MAX = 0, WK_NORM_MINMAX = 1, WK_NORM_MEAN = 2 } wk_norm_mode;
 
 typedef struct wk_compress_desc {
@@ -179,7 +179,7 @@ typedef struct wk_store_desc {
     int32_t H, d, dtype;
 } wk_store_desc;
 
-/* Window assembly (Sec. 1 "without re-encoding", Sec. 4.2): window = native rows followed by
+/* Window assembly (Sec. 1: retrieved caches are reused as stored, not re-encoded; Sec. 4.2): window = native rows followed by
  * the stored rows of each retrieved chunk in the order of ids, byte for byte, for K and V.
  * The addresses in K_ptr/V_ptr may point to HBM or to pinned+mapped host memory (CPU-offloaded
  * store, Sec. 7); ids and n_ids come from wk_score_chunks and are read on the device, so no
@@ -295,7 +295,7 @@ typedef struct wk_window_step {
  * Errors: INVALID_ARG, UNSUPPORTED (a count does not fit in 31 bits). */
 wk_status wk_window_plan(const wk_window_desc *w, int64_t chunk_index, wk_window_step *out);
 
-/* In-place refresh of the retrieved region (Sec. 4.2: the top-k chunks "fill this region").  slot_ids
+/* In-place refresh of the retrieved region (Sec. 4.2: the top-k chunks are what this region holds).  slot_ids
  * says which stored chunk each of the R slots holds (-1: none); ids are the chunks wanted now (from
  * wk_score_chunks or wk_score_chunks_query).  Ids that are out of range, repeat an earlier one, or
  * name a chunk whose n_tok differs from slot_tokens are dropped; n are left.  Afterwards exactly slots

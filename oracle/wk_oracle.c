@@ -39,7 +39,7 @@
  * Readings of silent points (each repeated where it is used):
  *   - zero-norm key: its cosine terms are 0;
  *   - ties in Eq. 5 scores / retrieval distances: lower index first;
- *   - "normalized across the retrieval candidate set": divide by the maximum
+ *   - normalisation of a distance term over the candidate set (Sec. 5.1): divide by the maximum
  *     over candidates (variants: min-max, mean).  Parity with the authors'
  *     normalisation is unpinned;
  *   - rotation = R_y(yaw) * R_x(pitch), no roll; geodesic = rotation angle of
@@ -195,7 +195,7 @@ static int cmp_i32(const void *a, const void *b)
     return (x > y) - (x < y);
 }
 
-/* "retain the bottom P%": the n_keep lowest scores, ties to the lower index;
+/* The lowest-scoring P% are the ones retained (Sec. 4.3): the n_keep lowest scores, ties to the lower index;
  * the kept indices are returned in ascending order. */
 int wko_select_lowest(const double *s, int64_t n, int64_t n_keep, int32_t *idx_out)
 {

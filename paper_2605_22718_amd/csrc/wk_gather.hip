@@ -1,4 +1,4 @@
-// Window assembly (paper Sec. 1 "without re-encoding", Sec. 4.2): the retrieved chunks' stored
+// Window assembly (paper Sec. 1: stored caches are reused as they are, not re-encoded; Sec. 4.2): the retrieved chunks' stored
 // K/V rows are placed behind the native sliding-window rows, byte for byte.
 //
 // In the head-major layout every (head, chunk) pair is one contiguous byte range, so the gather
