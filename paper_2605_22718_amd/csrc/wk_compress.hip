@@ -28,28 +28,55 @@ struct CompressDims {
     int n_keep, n_out;
 };
 
+// Rows kernels (norms, factored scores): 16 lanes share a 256- or 512-byte row.  With HS > 1 the heads of
+// a list are dealt round-robin to HS such lane groups (a whole wave per token at HS = 4), so that a token
+// whose vector spans many heads has its rows in flight from several groups at once; kHeadBatch rows
+// per group are requested before any is consumed.  Partial sums meet in a fixed order.
+constexpr int kHeadBatch = 5;
+
+template <int HS>
+__device__ inline double head_split_sum(double x) {
+    x = wk::row_group_sum(x);
+    if constexpr (HS >= 2) x += __shfl_xor(x, 16);
+    if constexpr (HS >= 4) x += __shfl_xor(x, 32);
+    return x;
+}
+
 // out[(b*G+g)*n_rows + i] = |key first_row + i|^2 over the heads of group g; src is [batch][H][rows_per_head][128]
-template <int DT>
+template <int DT, int HS>
 __global__ __launch_bounds__(256) void k_rows_normsq(const char *__restrict__ src, CompressDims p, int rows_per_head,
                                                      int first_row, int n_rows, double *__restrict__ out) {
-    const int i = blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const int i = blockIdx.x * (kRowsPerBlock / HS) + threadIdx.x / (kRowLanes * HS);
+    const int hq = (threadIdx.x / kRowLanes) % HS;
     const int sub = threadIdx.x % kRowLanes;
     const int g = blockIdx.y, b = blockIdx.z;
     if (i >= n_rows) return;
     const size_t row_bytes = WK_D * wk::esize(DT);
+    const size_t head_bytes = (size_t)rows_per_head * row_bytes;
+    const char *base = src + ((size_t)b * p.H * rows_per_head + first_row + i) * row_bytes;
     double acc = 0.0;
-    for (int hh = 0; hh < p.hg; ++hh) {
-        const int h = p.G == 1 ? hh : g;
-        const char *row = src + (((size_t)b * p.H + h) * rows_per_head + first_row + i) * row_bytes;
-        float v[8];
-        load_row8<DT>(row, sub, v);
-        float s = 0.f;
+    for (int hh0 = hq; hh0 < p.hg; hh0 += HS * kHeadBatch) {
+        float v[kHeadBatch][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s = fmaf(v[e], v[e], s);
-        acc += (double)s;
+        for (int u = 0; u < kHeadBatch; ++u) {
+            const int hh = hh0 + u * HS;
+            if (hh < p.hg) {
+                load_row8<DT>(base + (size_t)(p.G == 1 ? hh : g) * head_bytes, sub, v[u]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[u][e] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kHeadBatch; ++u) {
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s = fmaf(v[u][e], v[u][e], s);
+            acc += (double)s;
+        }
     }
-    acc = wk::row_group_sum(acc);
-    if (sub == 0) out[((size_t)b * p.G + g) * n_rows + i] = acc;
+    acc = head_split_sum<HS>(acc);
+    if (sub == 0 && hq == 0) out[((size_t)b * p.G + g) * n_rows + i] = acc;
 }
 
 // m[(b*H+h)*128 + c] = (1/T) sum_i A[b][h][i][c] / |anchor key i|   (fp32 result of an fp64 sum).
@@ -100,36 +127,53 @@ __global__ __launch_bounds__(WK_D) void k_anchor_mean_finish(const double *__res
 }
 
 // scores[(b*G+g)*n_cand + j] = (k_j . m) / |k_j|
-template <int DT>
+template <int DT, int HS>
 __global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__ K, CompressDims p,
                                                         const float *__restrict__ m,
                                                         double *__restrict__ scores) {
-    const int j = blockIdx.x * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const int j = blockIdx.x * (kRowsPerBlock / HS) + threadIdx.x / (kRowLanes * HS);
+    const int hq = (threadIdx.x / kRowLanes) % HS;
     const int sub = threadIdx.x % kRowLanes;
     const int g = blockIdx.y, b = blockIdx.z;
     if (j >= p.n_cand) return;
     const size_t row_bytes = WK_D * wk::esize(DT);
+    const size_t head_bytes = (size_t)p.n_tok * row_bytes;
+    const char *base = K + ((size_t)b * p.H * p.n_tok + p.first_cand + j) * row_bytes;
+    const float *mb = m + (size_t)b * p.H * WK_D + 8 * sub;
     double dacc = 0.0, nacc = 0.0;
-    for (int hh = 0; hh < p.hg; ++hh) {
-        const int h = p.G == 1 ? hh : g;
-        const char *row = K + (((size_t)b * p.H + h) * p.n_tok + p.first_cand + j) * row_bytes;
-        float v[8];
-        load_row8<DT>(row, sub, v);
-        const float4 *mp = reinterpret_cast<const float4 *>(m + ((size_t)b * p.H + h) * WK_D) + 2 * sub;
-        const float4 m0 = mp[0], m1 = mp[1];
-        const float mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-        float dp = 0.f, ns = 0.f;
+    for (int hh0 = hq; hh0 < p.hg; hh0 += HS * kHeadBatch) {
+        float v[kHeadBatch][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            dp = fmaf(v[e], mm[e], dp);
-            ns = fmaf(v[e], v[e], ns);
+        for (int u = 0; u < kHeadBatch; ++u) {
+            const int hh = hh0 + u * HS;
+            if (hh < p.hg) {
+                load_row8<DT>(base + (size_t)(p.G == 1 ? hh : g) * head_bytes, sub, v[u]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[u][e] = 0.f;
+            }
         }
-        dacc += (double)dp;
-        nacc += (double)ns;
+#pragma unroll
+        for (int u = 0; u < kHeadBatch; ++u) {
+            const int hh = hh0 + u * HS;
+            if (hh < p.hg) {
+                const float4 *mp = reinterpret_cast<const float4 *>(mb + (size_t)(p.G == 1 ? hh : g) * WK_D);
+                const float4 m0 = mp[0], m1 = mp[1];
+                const float mm[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+                float dp = 0.f, ns = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    dp = fmaf(v[u][e], mm[e], dp);
+                    ns = fmaf(v[u][e], v[u][e], ns);
+                }
+                dacc += (double)dp;
+                nacc += (double)ns;
+            }
+        }
     }
-    dacc = wk::row_group_sum(dacc);
-    nacc = wk::row_group_sum(nacc);
-    if (sub == 0) {
+    dacc = head_split_sum<HS>(dacc);
+    nacc = head_split_sum<HS>(nacc);
+    if (sub == 0 && hq == 0) {
         double s = nacc < 1e-60 ? 0.0 : dacc / sqrt(nacc);
         scores[((size_t)b * p.G + g) * p.n_cand + j] = s + 0.0;  // -0.0 -> +0.0
     }
@@ -330,9 +374,11 @@ __device__ inline int block_excl_scan(int v, int *wsum /*[kSelThreads/64]*/, int
     return off + x - v;
 }
 
-// One block per list.  Radix-select (8 passes of 8 bits over order-preserving 64-bit keys) finds
-// the n_keep-th smallest score tau; then tokens with score < tau, plus the first few (by index)
-// with score == tau, are written in ascending index order via block scans.  Lists of up to
+// One block per list.  Radix-select (up to 8 passes of 8 bits, from the top, over order-preserving
+// 64-bit keys) finds the n_keep-th smallest score tau; then tokens with score < tau, plus the first
+// few (by index) with score == tau, are written in ascending index order via block scans.  The passes
+// stop as soon as every key that shares tau's leading digits is kept anyway (for fp64 scores usually
+// after three or four digits); comparisons then look at those leading digits only.  Lists of up to
 // kSelLds keys are held in LDS for all passes; longer lists are re-read from global memory.
 constexpr int kSelLds = 6144;   // 48 KB of keys
 
@@ -341,7 +387,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict
     __shared__ uint64_t keys[kSelLds];
     __shared__ unsigned hist[256];
     __shared__ uint64_t s_prefix;
-    __shared__ int s_k;
+    __shared__ int s_k, s_cnt;
     __shared__ int wsum[kSelThreads / 64];
     const int list = blockIdx.x;  // b*G + g
     const double *s = scores + (size_t)list * p.n_cand;
@@ -359,6 +405,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict
 
     uint64_t prefix = 0;
     int k = p.n_keep;  // rank (1-based) still to locate among keys matching the prefix
+    int low = 0;       // digits below this bit were not needed to separate kept from dropped
     if (p.n_keep < n) {
         for (int pass = 7; pass >= 0; --pass) {
             const int shift = pass * 8;
@@ -387,26 +434,32 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const double *__restrict
                 for (int w = 0; w < (tid >> 6); ++w) incl += wsum[w];
                 if (incl >= k && incl - cnt < k) {   // exactly one bucket satisfies this
                     s_k = k - (incl - cnt);
+                    s_cnt = cnt;
                     s_prefix = prefix | ((uint64_t)tid << shift);
                 }
             }
             __syncthreads();
             k = s_k;
             prefix = s_prefix;
+            if (s_cnt == k) {   // the whole bucket is kept: nothing below this digit matters
+                low = shift;
+                break;
+            }
         }
     } else {
         prefix = ~0ull;  // keep everything: every key is below (or equal to) the largest key
         k = n;
     }
-    // prefix = tau, k = how many of the keys equal to tau are kept (lowest indices first)
+    // prefix = tau (its digits from bit `low` up), k = how many of the keys equal to it there are kept
+    // (lowest indices first)
     int eq_base = 0, out_base = 0;
     for (int j0 = 0; j0 < n; j0 += kSelThreads) {
         const int j = j0 + tid;
         bool less = false, eq = false;
         if (j < n) {
             const uint64_t key = key_at(j);
-            less = key < prefix;
-            eq = key == prefix;
+            less = (key >> low) < (prefix >> low);
+            eq = (key >> low) == (prefix >> low);
         }
         int eq_tot, keep_tot;
         const int eq_rank = eq_base + block_excl_scan(eq ? 1 : 0, wsum, eq_tot);
@@ -509,15 +562,24 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
     const char *A = reinterpret_cast<const char *>(d->anchor_mode == WK_ANCHOR_EXTERNAL ? K_anchor : K);
     const char *Kc = reinterpret_cast<const char *>(K);
     if (p.n_cand > 0) {  // scores are always produced: callers may read them from the workspace
-        dim3 g1((p.T + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
-        hipLaunchKernelGGL(k_rows_normsq<DT>, g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
+        // a token's vector spans hg heads: with four or more, a wave per token (heads dealt to its four
+        // 16-lane groups), otherwise 16 lanes per token
+        const bool split = p.hg >= 4;
+        const int rows_pb = split ? kRowsPerBlock / 4 : kRowsPerBlock;
+        dim3 g1((p.T + rows_pb - 1) / rows_pb, p.G, d->batch);
+        if (split) hipLaunchKernelGGL((k_rows_normsq<DT, 4>), g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
+        else hipLaunchKernelGGL((k_rows_normsq<DT, 1>), g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
         WK_LAUNCH_CHECK();
         if (d->score_algo == WK_SCORE_GEMM) {
             if constexpr (DT == WK_BF16) {
                 double *nsq_cand = reinterpret_cast<double *>(wsp + ws.nsq_cand);
-                dim3 g2((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
-                hipLaunchKernelGGL(k_rows_normsq<DT>, g2, dim3(256), 0, st, Kc, p, p.n_tok, p.first_cand, p.n_cand,
-                                   nsq_cand);
+                dim3 g2((p.n_cand + rows_pb - 1) / rows_pb, p.G, d->batch);
+                if (split)
+                    hipLaunchKernelGGL((k_rows_normsq<DT, 4>), g2, dim3(256), 0, st, Kc, p, p.n_tok, p.first_cand,
+                                       p.n_cand, nsq_cand);
+                else
+                    hipLaunchKernelGGL((k_rows_normsq<DT, 1>), g2, dim3(256), 0, st, Kc, p, p.n_tok, p.first_cand,
+                                       p.n_cand, nsq_cand);
                 WK_LAUNCH_CHECK();
                 // one workgroup per (candidate block, anchor block); beyond 8 anchor blocks a workgroup
                 // walks several
@@ -555,8 +617,9 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
             WK_LAUNCH_CHECK();
             hipLaunchKernelGGL(k_anchor_mean_finish, dim3(p.H, d->batch), dim3(WK_D), 0, st, mean_partial, p, mean);
             WK_LAUNCH_CHECK();
-            dim3 g3((p.n_cand + kRowsPerBlock - 1) / kRowsPerBlock, p.G, d->batch);
-            hipLaunchKernelGGL(k_score_factored<DT>, g3, dim3(256), 0, st, Kc, p, mean, scores);
+            dim3 g3((p.n_cand + rows_pb - 1) / rows_pb, p.G, d->batch);
+            if (split) hipLaunchKernelGGL((k_score_factored<DT, 4>), g3, dim3(256), 0, st, Kc, p, mean, scores);
+            else hipLaunchKernelGGL((k_score_factored<DT, 1>), g3, dim3(256), 0, st, Kc, p, mean, scores);
             WK_LAUNCH_CHECK();
         }
     }
