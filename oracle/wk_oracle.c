@@ -10,7 +10,7 @@
  * patterns); every value is widened to double before any arithmetic.
  *
  *   wko_compress_scores / wko_select_lowest / wko_compress
- *        World Compression, Sec. 4.3, Eq. 5 and the "bottom P%" rule.
+ *        World Compression, Sec. 4.3, Eq. 5 and the rule that the lowest-scoring P% are kept.
  *   wko_keep_count
  *        token counts of a compressed chunk (Sec. 4.3, Sec. 5.1, Sec. 5.4).
  *   wko_score_chunks
@@ -340,9 +340,9 @@ int wko_score_chunks(const float *poses, int M, const float *cur, int norm_mode,
     return 0;
 }
 
-/* Query-based retrieval (Sec. 4.2: the relevance function may be a "query-based importance
- * score"; App. C: stored chunks ranked "by their attention scores with respect to the current
- * denoising query").  Reading: the relevance of chunk c is the attention mass its keys receive from
+/* Query-based retrieval (Sec. 4.2 allows an importance score computed from the queries as the
+ * relevance function; App. C ranks the stored chunks by how strongly the queries of the chunk being
+ * denoised attend to them, without a formula).  Reading: the relevance of chunk c is the attention mass its keys receive from
  * the current queries in one softmax over the keys of all M candidate chunks, averaged over heads
  * and query rows; the min(R, M) chunks of largest mass are returned, ties to the lower chunk id.
  * Parity with the authors' exact score (which layers, heads or queries they average) is unpinned.

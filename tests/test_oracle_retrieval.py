@@ -124,6 +124,10 @@ def test_accumulate_actions_closed_cases():
     deg15 = math.radians(15)
     p = oracle.accumulate_actions([YP] * 4 + [W])
     np.testing.assert_allclose(p[-1], [math.sin(4 * deg15), 0, math.cos(4 * deg15), 4 * deg15, 0], atol=1e-6)
+    p = oracle.accumulate_actions([YM] * 2 + [W])   # yaw- turns the heading towards -x
+    np.testing.assert_allclose(p[-1], [-math.sin(2 * deg15), 0, math.cos(2 * deg15), -2 * deg15, 0], atol=1e-6)
+    p = oracle.accumulate_actions([YM, YP, PM, PP])
+    np.testing.assert_allclose(p[-1], 0, atol=1e-7)
     p = oracle.accumulate_actions([W, W, S, S])
     np.testing.assert_allclose(p[-1], 0, atol=1e-7)
     np.testing.assert_allclose(p[1], [0, 0, 2, 0, 0], atol=1e-7)
