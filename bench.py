@@ -237,6 +237,19 @@ def main():
         "gather_hbm_GBps": gather_bytes / (per_call["gather_hbm"] * 1e-3) / 1e9,
     }
 
+    if cfg.dtype == ws.configs.DT_BF16:
+        # the HBM-resident store attended in place (no window copy): gather + attention as one call
+        O2 = torch.empty_like(O)
+        wk.wk_attention_in_place(Q, Kw, Vw, cfg.n_native, store.desc, ids, n_found, cfg.R, O2)
+        torch.cuda.synchronize()
+        assert (O2.float() - O.float()).abs().max().item() <= 4e-3      # same window, key tiles cut per chunk
+        t_ip = time_call(lambda: wk.wk_attention_in_place(Q, Kw, Vw, cfg.n_native, store.desc, ids, n_found, cfg.R,
+                                                          O2), reps)
+        extra["attention_in_place"] = {
+            "ms": t_ip, "ms_gather_plus_attention": per_call["gather_hbm"] + att_ms,
+            "note": "not part of `value`: the timed step assembles the window with wk_gather_window"}
+        del O2
+
     if cfg.q_frames > 1 and N_kv >= 2 * cfg.N_q:
         # option: frame-level causal mask inside the denoising chunk, placed behind a sink chunk of the same
         # size (the window manager's layout); same window, so the flop count is that of the unmasked call

@@ -246,6 +246,30 @@ wk_status wk_attention_block_causal(const void *Q, const void *K_win, const void
                                     void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t wk_attention_block_causal_workspace_bytes(int32_t H, int32_t N_q);
 
+/* wk_gather_window and wk_attention in one: attention over the window of Sec. 4.2 without building it.
+ * The window is the native rows followed by the stored rows of chunks ids[0 .. min(*n_ids, R_max)),
+ * exactly what wk_gather_window would assemble (the stored caches are used as they are, Sec. 1), but
+ * the kernel reads each retrieved chunk where the store keeps it.  Meant for a store that lives in
+ * HBM, where copying 2 x R chunks per layer and step costs more than the indirection; a store in pinned
+ * host memory is better served by wk_gather_window / wk_prefetch_gather, which cross the host link once.
+ * bf16 only.  The result equals wk_attention over the assembled window up to the order of fp32 sums
+ * (key tiles are cut per segment here).
+ *
+ *   Q          device, [H][N_q][d]; H, d and the element type are the store's
+ *   K_native,V_native device, [H][native_row_stride][d]; the first n_native rows of each head are
+ *              attended.  May be NULL when n_native is 0.
+ *   ids,n_ids  device; as for wk_gather_window (ids outside [0, M) and empty chunks are skipped,
+ *              n_ids NULL means R_max)
+ *   O          device out, [H][N_q][d] bf16; all zero when the window is empty
+ *   lse        device out, [H][N_q] float or NULL; -inf when the window is empty
+ *   scale      logit scale; 0 means 1/sqrt(d)
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, fp32 store, R_max > 32, 2^23 or more rows in the
+ *         native part or in a chunk), SHAPE (n_native > native_row_stride). */
+wk_status wk_attention_in_place(const void *Q, const void *K_native, const void *V_native,
+                                int32_t n_native, int32_t native_row_stride, const wk_store_desc *store,
+                                const int32_t *ids, const int32_t *n_ids, int32_t R_max, void *O,
+                                float *lse, int32_t N_q, float scale, void *hip_stream);
+
 /* First half of query-based retrieval (Sec. 4.2, App. C): the log-sum-exp of the current queries'
  * scaled logits against the stored keys of every chunk of the store, all chunks in one launch.
  * The result is the `lse` input of wk_score_chunks_query.  Only K_ptr, n_tok, M, H, d and dtype

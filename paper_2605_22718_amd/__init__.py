@@ -32,6 +32,7 @@ EXPORTS = [
     "wk_prefetch_create", "wk_prefetch_destroy", "wk_prefetch_stream", "wk_prefetch_after", "wk_prefetch_gather",
     "wk_prefetch_acquire", "wk_prefetch_release",
     "wk_accumulate_actions", "wk_gather_window", "wk_attention", "wk_attention_workspace_bytes",
+    "wk_attention_in_place",
     "wk_host_device_pointer", "wk_calibration_copy",
     "wk_status_string",
 ]
@@ -86,6 +87,9 @@ def lib():
                                         vp, C.c_size_t, vp]
         L.wk_score_chunks.restype = C.c_int
         L.wk_score_chunks.argtypes = [vp, i32, C.POINTER(f32), i32, i32, vp, vp, vp, vp]
+        L.wk_attention_in_place.restype = C.c_int
+        L.wk_attention_in_place.argtypes = [vp, vp, vp, i32, i32, C.POINTER(wk_store_desc), vp, vp, i32, vp, vp, i32,
+                                            f32, vp]
         L.wk_score_chunks_query.restype = C.c_int
         L.wk_score_chunks_query.argtypes = [vp, i32, C.c_int64, i32, vp, vp, vp, vp, C.c_size_t, vp]
         L.wk_score_chunks_query_workspace_bytes.restype = C.c_size_t
@@ -300,6 +304,18 @@ def wk_chunk_lse(store_desc: wk_store_desc, Q, lse_out, scale=0.0):
                             _dev(lse_out, "lse_out", torch.float32), _stream())
     _check(st, "wk_chunk_lse")
     return lse_out
+
+
+def wk_attention_in_place(Q, K_native, V_native, n_native, store_desc: wk_store_desc, ids, n_ids, R_max, O, lse=None,
+                          scale=0.0):
+    """wk_attention_in_place.  K_native/V_native [H][stride][d] (or None with n_native = 0); ids/n_ids device int32."""
+    stride = K_native.shape[1] if K_native is not None else 0
+    st = lib().wk_attention_in_place(_dev(Q, "Q"), _dev(K_native, "K_native"), _dev(V_native, "V_native"), n_native,
+                                     stride, C.byref(store_desc), _dev(ids, "ids", torch.int32),
+                                     _dev(n_ids, "n_ids", torch.int32), R_max, _dev(O, "O"),
+                                     _dev(lse, "lse", torch.float32), Q.shape[1], scale, _stream())
+    _check(st, "wk_attention_in_place")
+    return O
 
 
 def wk_window_plan(desc: wk_window_desc, chunk_index: int) -> wk_window_step:

@@ -50,6 +50,13 @@ struct AttnArgs {
     // window (only used to convert *n_kv_dev); part_slot >= 0 makes it write its (O, max, sum)
     // as split `part_slot` for k_attn_merge instead of a final result.
     int q_rows, q_off, kv_start, part_slot;
+    // attention in place over the store (k_attn_bf16<.., IN_PLACE>): the window is K/V above (N_kv native
+    // rows, may be 0) followed by the stored chunks ids[0 .. min(*n_ids, R_max)), read where they are
+    // stored: chunk c has keys k_table[c] and values v_table[c], both [H][n_tok[c]][128].
+    const void *const *v_table;
+    const int32_t *ids;
+    const int32_t *n_ids;
+    int R_max, store_M;
 };
 
 constexpr int kXcds = 8;
@@ -325,16 +332,75 @@ __device__ inline float max_across_halves(float x) {
 #define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
-template <int WAVES, bool MULTI>
+// IN_PLACE: the window is a list of segments (the native rows, then each retrieved chunk where the store
+// keeps it) instead of one array.  Tiles never straddle segments: a segment's last tile may be partial and
+// is masked like the window's last tile; a wave-uniform cursor walks the list.
+constexpr int kMaxSegments = 33;   // native rows + up to 32 retrieved chunks
+struct Segment { const char *K; const char *V; int len; int pad; };
+
+__device__ inline const char *uniform_ptr(const char *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+}
+
+template <int WAVES, bool MULTI, bool IN_PLACE>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTable sub) {
     static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
+    static_assert(!(MULTI && IN_PLACE), "a table of launches over one window array only");
     extern __shared__ __attribute__((aligned(256))) char smem[];
     int c, h, qt, sp;
     if (!select_work<MULTI>(a, sub, 256, c, h, qt, sp)) return;
     const Window win = window_of(a, c);
-    const int n_kv = win.n_kv;
     float *const lse = win.lse;
     const int tid = threadIdx.x, lane = tid & 63;
+    // segment list of this head and its number of tiles
+    int n_seg = 0, seg_tiles = 0;
+    const Segment *seg_list = nullptr;
+    if constexpr (IN_PLACE) {
+        __shared__ Segment segs[kMaxSegments];
+        __shared__ Segment raw[kMaxSegments];
+        __shared__ int seg_meta[2];
+        // entry 0 = native rows, entry 1 + r = retrieved chunk r; one thread each fetches its entry (the
+        // id, then the chunk's length and addresses), thread 0 then drops the empty ones
+        if (tid <= a.R_max) {
+            Segment e{nullptr, nullptr, 0, 0};
+            if (tid == 0) {
+                if (a.N_kv > 0)
+                    e = Segment{a.K + (size_t)h * a.kv_row_stride * 256, a.V + (size_t)h * a.kv_row_stride * 256, a.N_kv, 0};
+            } else {
+                int nf = a.n_ids ? *a.n_ids : a.R_max;
+                nf = nf < a.R_max ? nf : a.R_max;
+                const int id = tid - 1 < nf ? a.ids[tid - 1] : -1;
+                if (id >= 0 && id < a.store_M) {
+                    const int len = a.n_tok[id];
+                    if (len > 0)
+                        e = Segment{reinterpret_cast<const char *>(a.k_table[id]) + (size_t)h * len * 256,
+                                    reinterpret_cast<const char *>(a.v_table[id]) + (size_t)h * len * 256, len, 0};
+                }
+            }
+            raw[tid] = e;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int n = 0, tiles = 0;
+            for (int r = 0; r <= a.R_max; ++r) {
+                const Segment e = raw[r];
+                if (e.len > 0) {
+                    segs[n++] = e;
+                    tiles += (e.len + 63) / 64;
+                }
+            }
+            seg_meta[0] = n;
+            seg_meta[1] = tiles;
+        }
+        __syncthreads();
+        n_seg = __builtin_amdgcn_readfirstlane(seg_meta[0]);
+        seg_tiles = __builtin_amdgcn_readfirstlane(seg_meta[1]);
+        seg_list = segs;
+    }
+    const int n_kv = IN_PLACE ? seg_tiles * 64 : win.n_kv;   // IN_PLACE: only its tile count is used
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
     const int q = qt * (WAVES * 32) + wave * 32 + col;
@@ -411,9 +477,65 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
 
     // Loads: 2 per wave for a K tile, 2 for a V tile (rel = tile index relative to t0).  Rows past the
     // window clamp to the last key; those keys are masked (weight exactly 0) before they can contribute.
+    // IN_PLACE: one cursor walks the segment list in steps of a tile, at the K loads, which lead
+    // everything else.  What later stages need of a tile is kept from the moment its K tile was requested:
+    // the V tile is requested one K request later (two-deep line of its address and bounds) and S^T of
+    // the tile is formed three K requests later (four-deep line of its number of valid keys).  Moving past
+    // the list's last tile leaves the cursor on it (the look-ahead fetches it again and nobody reads it).
+    // All of this is wave-uniform scalar state.
+    struct TileRef { const char *base; int row, len; };
+    const char *cur_k = nullptr, *cur_v = nullptr;
+    int cur_len = 0, cur_row = 0, cur_seg = 0;
+    TileRef v_line[2] = {{nullptr, 0, 0}, {nullptr, 0, 0}};
+    int valid_line[4] = {0, 0, 0, 0};
+    if constexpr (IN_PLACE) {
+        if (n_seg > 0) {
+            cur_len = __builtin_amdgcn_readfirstlane(seg_list[0].len);
+            cur_k = uniform_ptr(seg_list[0].K);
+            cur_v = uniform_ptr(seg_list[0].V);
+        }
+    }
+    // one tile: rows past the segment's end clamp to its last row (those keys are masked when consumed)
+    auto issue_at = [&](const char *base, int row, int len, const unsigned (&src)[2], char *dst) {
+        const unsigned t_off = (unsigned)row * 256u;
+        if (row + kKeys <= len) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                __builtin_amdgcn_global_load_lds(WK_GLB(base + (t_off + src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
+        } else {
+            const unsigned seg_last = (unsigned)(len - 1) * 256u;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const unsigned o = min(t_off + src[i], seg_last + (src[i] & 255u));
+                __builtin_amdgcn_global_load_lds(WK_GLB(base + o), WK_LDS(dst + i * 1024), 16, 0, 0);
+            }
+        }
+    };
+    auto issue_k_in_place = [&](char *dst) {
+        issue_at(cur_k, cur_row, cur_len, k_src, dst);
+        v_line[1] = v_line[0];
+        v_line[0] = TileRef{cur_v, cur_row, cur_len};
+        valid_line[3] = valid_line[2];
+        valid_line[2] = valid_line[1];
+        valid_line[1] = valid_line[0];
+        valid_line[0] = cur_len - cur_row;   // 64 or more: a full tile
+        if (cur_row + kKeys < cur_len) {
+            cur_row += kKeys;
+        } else if (cur_seg + 1 < n_seg) {
+            ++cur_seg;
+            cur_row = 0;
+            cur_len = __builtin_amdgcn_readfirstlane(seg_list[cur_seg].len);
+            cur_k = uniform_ptr(seg_list[cur_seg].K);
+            cur_v = uniform_ptr(seg_list[cur_seg].V);
+        }
+    };
     auto issue_k = [&](int rel, int slot) {
         const unsigned t_off = (unsigned)(t0 + rel) * (kKeys * 256u);
         char *dst = dma_dst + slot * kTileBytes;
+        if constexpr (IN_PLACE) {
+            issue_k_in_place(dst);
+            return;
+        }
         if ((t0 + rel + 1) * kKeys <= n_kv) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -429,6 +551,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     auto issue_v = [&](int rel, int slot) {
         const unsigned t_off = (unsigned)(t0 + rel) * (kKeys * 256u);
         char *dst = dma_dst + slot * kTileBytes + kVRing;
+        if constexpr (IN_PLACE) {
+            issue_at(v_line[1].base, v_line[1].row, v_line[1].len, v_src, dst);
+            return;
+        }
         if ((t0 + rel + 1) * kKeys <= n_kv) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -463,6 +589,18 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
                 const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(k_rd[st] + byte_off + b * 8192);
                 s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[st], s[b], 0, 0, 0);
             }
+    };
+    // IN_PLACE: the tile whose S^T has just been formed had its K tile requested three requests ago; keys
+    // past its segment's end get -inf (weight exactly 0).
+    auto mask_segment_tail = [&](f32x16 (&s)[2]) {
+        const int valid = valid_line[3];
+        if (valid < kKeys) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (32 * b + 8 * (r >> 2) + 4 * g + (r & 3) >= valid) s[b][r] = -INFINITY;
+        }
     };
     // scaled row max of a tile's raw logits (both lane halves combined)
     auto tile_max = [&](const f32x16 (&s)[2]) {
@@ -553,8 +691,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     }
     f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
     float mt;
-    if (sh & 1) { compute_s(sh * kTileBytes, s_b); mt = tile_max(s_b); }
-    else        { compute_s(sh * kTileBytes, s_a); mt = tile_max(s_a); }
+    if (sh & 1) {
+        compute_s(sh * kTileBytes, s_b);
+        if constexpr (IN_PLACE) mask_segment_tail(s_b);
+        mt = tile_max(s_b);
+    } else {
+        compute_s(sh * kTileBytes, s_a);
+        if constexpr (IN_PLACE) mask_segment_tail(s_a);
+        mt = tile_max(s_a);
+    }
     __syncthreads();   // K tile 0 has been read by every wave: step 0 may load K tile 4 into its slot
 
     // one pipeline step: tile j (ring position POS) is consumed, S^T of tile j+1 produced
@@ -566,6 +711,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         compute_s(((POS + 1) & 3) * kTileBytes, s_next);
         bf16x8 pb[4];
         probabilities(s_cur, pb);
+        // (the rare branch sits between the two matrix products, so that the row max below can still be
+        // interleaved with the second one)
+        if constexpr (IN_PLACE) mask_segment_tail(s_next);
         accumulate_pv(POS * kTileBytes, pb);
         mt = tile_max(s_next);
         __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): all but the loads of this step and the one before have landed
@@ -591,7 +739,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     // past the window and redo its max.
     {
         const int kt = (t1 - 1) * kKeys;
-        if (kt + kKeys > n_kv) {
+        if (!IN_PLACE && kt + kKeys > n_kv) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -868,9 +1016,11 @@ size_t split_workspace_bytes(int H, int N_q, int splits) {
 wk_status allow_large_lds() {
     static bool done = false;
     if (!done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, true>),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, true, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
             return WK_ERR_HIP;
         done = true;
@@ -895,7 +1045,7 @@ wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipSt
     const wk_status lds_rc = allow_large_lds();
     if (lds_rc != WK_OK) return lds_rc;
     if (a.O)
-        hipLaunchKernelGGL((k_attn_bf16<WAVES, false>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a,
+        hipLaunchKernelGGL((k_attn_bf16<WAVES, false, false>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a,
                            SubTable{});
     else
         hipLaunchKernelGGL(k_lse_bf16, dim3(a.per_xcd * kXcds), dim3(512), kVRing, st, a);
@@ -940,6 +1090,7 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     a.n_tok = nullptr;
     a.n_chunks = 0;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
+    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     if (dtype == WK_F32) {
         const int q_per_wg = kF32Waves * 32;
@@ -969,7 +1120,8 @@ wk_status launch_plain(AttnArgs a, int dtype, hipStream_t st) {
         a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
         const wk_status rc = allow_large_lds();
         if (rc != WK_OK) return rc;
-        hipLaunchKernelGGL((k_attn_bf16<8, false>), dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a, SubTable{});
+        hipLaunchKernelGGL((k_attn_bf16<8, false, false>), dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a,
+                           SubTable{});
     }
     WK_LAUNCH_CHECK();
     return WK_OK;
@@ -1022,6 +1174,7 @@ extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win,
                                           wk::align_up((size_t)2 * H * N_q * WK_D * sizeof(float), 256));
     a.k_table = nullptr; a.n_tok = nullptr; a.n_chunks = 0;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
+    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
 
     const int frames = N_q / frame_T;
@@ -1049,7 +1202,7 @@ extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win,
         } else {
             const wk_status lrc = allow_large_lds();
             if (lrc != WK_OK) return lrc;
-            hipLaunchKernelGGL((k_attn_bf16<8, true>), dim3(g.per_xcd * kXcds), dim3(512), kSmemBytes, st, g, t);
+            hipLaunchKernelGGL((k_attn_bf16<8, true, false>), dim3(g.per_xcd * kXcds), dim3(512), kSmemBytes, st, g, t);
         }
         WK_LAUNCH_CHECK();
     } else {
@@ -1108,6 +1261,7 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
     a.n_tok = store->n_tok;
     a.n_chunks = store->M;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
+    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int q_per_wg = (store->dtype == WK_F32 ? kF32Waves : 8) * 32;
     const long long items = (long long)store->M * store->H * ((N_q + q_per_wg - 1) / q_per_wg);
@@ -1120,6 +1274,53 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
         return WK_OK;
     }
     return launch_bf16<8>(a, nullptr, 0, st);
+}
+
+extern "C" wk_status wk_attention_in_place(const void *Q, const void *K_native, const void *V_native,
+                                           int32_t n_native, int32_t native_row_stride,
+                                           const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids,
+                                           int32_t R_max, void *O, float *lse, int32_t N_q, float scale,
+                                           void *hip_stream) {
+    if (!store || !Q || !O) return WK_ERR_INVALID_ARG;
+    if (store->M < 0 || store->H < 1 || store->max_tok < 0 || N_q < 0 || R_max < 0 || n_native < 0)
+        return WK_ERR_INVALID_ARG;
+    if (store->dtype != WK_F32 && store->dtype != WK_BF16) return WK_ERR_INVALID_ARG;
+    if (!(scale >= 0.f) || std::isinf(scale)) return WK_ERR_INVALID_ARG;
+    if (n_native > 0 && (!K_native || !V_native)) return WK_ERR_INVALID_ARG;
+    if (R_max > 0 && store->M > 0 && (!ids || !store->K_ptr || !store->V_ptr || !store->n_tok))
+        return WK_ERR_INVALID_ARG;
+    if (store->d != WK_D || store->dtype != WK_BF16) return WK_ERR_UNSUPPORTED;
+    if (R_max > kMaxSegments - 1) return WK_ERR_UNSUPPORTED;
+    if (n_native >= (1 << 23) || store->max_tok >= (1 << 23)) return WK_ERR_UNSUPPORTED;   // 32-bit byte offsets
+    if (n_native > native_row_stride) return WK_ERR_SHAPE;
+    if (N_q == 0) return WK_OK;
+    if ((long long)store->H * ((N_q + 255) / 256) + kXcds > 0x7fffffffLL) return WK_ERR_UNSUPPORTED;
+    AttnArgs a;
+    a.Q = reinterpret_cast<const char *>(Q);
+    a.K = reinterpret_cast<const char *>(K_native);
+    a.V = reinterpret_cast<const char *>(V_native);
+    a.O = reinterpret_cast<char *>(O);
+    a.lse = lse;
+    a.H = store->H; a.N_q = N_q; a.N_kv = n_native; a.kv_row_stride = native_row_stride;
+    const float sc = scale == 0.f ? 1.f / std::sqrt((float)WK_D) : scale;
+    a.scale_log2 = sc * 1.4426950408889634f;
+    a.n_kv_dev = nullptr;
+    a.splits = 1;
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
+    a.k_table = store->K_ptr;
+    a.n_tok = store->n_tok;
+    a.n_chunks = 0;
+    a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
+    a.v_table = store->V_ptr; a.ids = ids; a.n_ids = n_ids; a.R_max = store->M > 0 ? R_max : 0; a.store_M = store->M;
+    a.n_qtiles = (N_q + 255) / 256;
+    a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
+    const wk_status rc = allow_large_lds();
+    if (rc != WK_OK) return rc;
+    hipLaunchKernelGGL((k_attn_bf16<8, false, true>), dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes,
+                       reinterpret_cast<hipStream_t>(hip_stream), a, SubTable{});
+    WK_LAUNCH_CHECK();
+    return WK_OK;
 }
 
 extern "C" size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype) {

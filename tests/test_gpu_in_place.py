@@ -1,0 +1,119 @@
+"""GPU parity of wk_attention_in_place: attention over the native rows and the retrieved chunks read where
+the store keeps them, against the oracle's gather followed by its attention (Sec. 4.2)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_22718_amd as wk
+import wk_synth as ws
+from wkt import ATT_MAX_ABS_BF16, ATT_MEAN_ABS_BF16, attention_errors, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _store(cfg, lengths):
+    ks, vs = [], []
+    for c, n in enumerate(lengths):
+        k, v = ws.make_native(cfg.with_(index=70 + c), n_rows=n)
+        ks.append(k), vs.append(v)
+    return ks, vs, wk.Store([k.to(dev()) for k in ks], [v.to(dev()) for v in vs])
+
+
+def _run(cfg, Q, Kn, Vn, n_native, store, ids, n_ids, R_max, want_lse=True):
+    d = dev()
+    O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=d)
+    lse = torch.full(Q.shape[:2], float("nan"), dtype=torch.float32, device=d) if want_lse else None
+    ids_d = torch.tensor(list(ids) + [0] * (R_max - len(ids)), dtype=torch.int32, device=d) if R_max else None
+    n_ids_d = None if n_ids is None else torch.tensor([n_ids], dtype=torch.int32, device=d)
+    wk.wk_attention_in_place(Q.to(d), None if Kn is None else Kn.to(d), None if Vn is None else Vn.to(d), n_native,
+                             store.desc, ids_d, n_ids_d, R_max, O, lse)
+    torch.cuda.synchronize()
+    return O, lse
+
+
+def _check(Q, ks, vs, ids, Kn, Vn, n_native, O, lse, rows=None):
+    Knn = None if Kn is None or n_native == 0 else Kn[:, :n_native].contiguous()
+    Vnn = None if Vn is None or n_native == 0 else Vn[:, :n_native].contiguous()
+    cap = n_native + sum(ks[i].shape[1] for i in ids)
+    Kw, Vw, n_win = oracle.gather(ks, vs, ids, Knn, Vnn, cap)
+    assert n_win == cap
+    ref, ref_lse = oracle.attention(Q, Kw, Vw, rows=rows, want_lse=True)
+    Og = O if rows is None else O[:, torch.as_tensor(rows, dtype=torch.long)]
+    mx, mean = attention_errors(Og, ref)
+    assert mx <= ATT_MAX_ABS_BF16 and mean <= ATT_MEAN_ABS_BF16, (mx, mean)
+    lg = lse.cpu().numpy().astype(np.float64)
+    lg = lg if rows is None else lg[:, rows]
+    assert np.abs(lg - ref_lse).max() <= 2e-2
+    return Kw, Vw
+
+
+def test_ragged_chunks_match_oracle_and_the_assembled_window():
+    cfg = ws.get_config(1).with_(H=3)
+    lengths = [5, 300, 77, 1, 129, 64, 128, 63]
+    ks, vs, store = _store(cfg, lengths)
+    Q = ws.make_queries(cfg, n_q=300)
+    Kn, Vn = ws.make_native(cfg, n_rows=140)                 # stride 140, of which 131 rows are attended
+    for ids in ([1, 0, 5, 2], [3], [4, 4, 1, 6, 7, 3], [6], [7, 5]):
+        O, lse = _run(cfg, Q, Kn, Vn, 131, store, ids, len(ids), 8)
+        Kw, Vw = _check(Q, ks, vs, ids, Kn, Vn, 131, O, lse)
+        # the same window assembled by the oracle and attended by wk_attention: same math, other tile cuts
+        O2 = torch.empty_like(O)
+        wk.wk_attention(Q.to(dev()), Kw.to(dev()), Vw.to(dev()), O2, None)
+        torch.cuda.synchronize()
+        assert (O.float() - O2.float()).abs().max().item() <= 4e-3
+
+
+def test_skipped_ids_device_count_and_empty_parts():
+    cfg = ws.get_config(1).with_(H=2)
+    ks, vs, store = _store(cfg, [40, 0, 200, 65])
+    Q = ws.make_queries(cfg, n_q=70)
+    Kn, Vn = ws.make_native(cfg, n_rows=33)
+    # ids outside the store and empty chunks are skipped; n_ids = NULL uses all R_max entries
+    O, lse = _run(cfg, Q, Kn, Vn, 33, store, [2, -1, 99, 1, 0], None, 5)
+    _check(Q, ks, vs, [2, 0], Kn, Vn, 33, O, lse)
+    # the device-side count cuts the list
+    O, lse = _run(cfg, Q, Kn, Vn, 33, store, [3, 2, 0], 1, 3)
+    _check(Q, ks, vs, [3], Kn, Vn, 33, O, lse)
+    # no native rows
+    O, lse = _run(cfg, Q, None, None, 0, store, [0, 3], 2, 2)
+    _check(Q, ks, vs, [0, 3], None, None, 0, O, lse)
+    # nothing retrieved: sliding-window attention
+    O, lse = _run(cfg, Q, Kn, Vn, 33, store, [], 0, 0)
+    ref = oracle.attention(Q, Kn, Vn)
+    mx, mean = attention_errors(O, ref)
+    assert mx <= ATT_MAX_ABS_BF16 and mean <= ATT_MEAN_ABS_BF16
+    # an empty window: zeros and -inf
+    O, lse = _run(cfg, Q, None, None, 0, store, [1, 9], 2, 2)
+    assert (O == 0).all() and torch.isinf(lse).all() and (lse < 0).all()
+
+
+def test_argument_errors():
+    cfg = ws.get_config(1).with_(H=2)
+    ks, vs, store = _store(cfg, [40])
+    Q = ws.make_queries(cfg, n_q=8).to(dev())
+    O = torch.empty_like(Q)
+    ids = torch.zeros(40, dtype=torch.int32, device=dev())
+    with pytest.raises(wk.WkError):
+        wk.wk_attention_in_place(Q, None, None, 5, store.desc, ids, None, 1, O)        # native rows announced, none given
+    with pytest.raises(wk.WkError):
+        wk.wk_attention_in_place(Q, None, None, 0, store.desc, ids, None, 33, O)       # more chunks than the kernel lists
+    with pytest.raises(wk.WkError):
+        wk.wk_attention_in_place(Q, None, None, 0, store.desc, None, None, 1, O)       # ids missing
+
+
+@pytest.mark.parametrize("ci", [1, 2])
+def test_full_size_sampled_rows(ci):
+    """Configs 1 and 2 at full size, the store in HBM: sampled query rows against the oracle."""
+    cfg = ws.get_config(ci)
+    n_out, _ = wk.wk_keep_count(cfg.rho, cfg.ratio_kind, cfg.anchor_mode, cfg.F, cfg.T)
+    lengths = [n_out] * cfg.R
+    ks, vs, store = _store(cfg, lengths)
+    Q = ws.make_queries(cfg)
+    Kn, Vn = ws.make_native(cfg)
+    ids = list(range(cfg.R))[::-1]
+    O, lse = _run(cfg, Q, Kn, Vn, cfg.n_native, store, ids, cfg.R, cfg.R)
+    assert not torch.isnan(O.float()).any()
+    rng = np.random.default_rng(ci)
+    rows = sorted(set([0, 255, 256, cfg.N_q - 1] + rng.integers(0, cfg.N_q, 12).tolist()))
+    _check(Q, ks, vs, ids, Kn, Vn, cfg.n_native, O, lse, rows=rows)
