@@ -212,7 +212,7 @@ wk_status wk_gather_window(const wk_store_desc *store, const int32_t *ids, const
  *   n_kv_dev   device, int32 or NULL.  If given, min(N_kv, *n_kv_dev) keys are attended (the
  *              length wk_gather_window wrote), read on the device.  A length of 0 gives O = 0
  *              and lse = -inf.
- *   workspace  device, 256-byte aligned, or NULL.  When H * ceil(N_q / 256) workgroups would leave
+ *   workspace  device, 256-byte aligned, or NULL.  When one workgroup per head and query tile would leave
  *              compute units idle (few heads, short query chunk, long window) the key range is split
  *              over several workgroups whose partial results are merged by a second kernel; that
  *              needs wk_attention_workspace_bytes(...) bytes.  Without (enough) workspace the call

@@ -183,10 +183,15 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a, SubTabl
     const float *Qrow = reinterpret_cast<const float *>(a.Q) + qrow * WK_D;
     float *Orow = reinterpret_cast<float *>(a.O) + qrow * WK_D;
     const bool with_o = a.O != nullptr;   // false: log-sum-exp only, V is not read (zeros stand in)
-    const bool partial_out = a.part_slot >= 0;
-    const size_t prow = ((size_t)(partial_out ? a.part_slot : 0) * a.H + h) * a.q_rows + a.q_off + q_ld;
+    const bool partial_out = a.part_slot >= 0 || a.splits > 1;
+    const size_t prow = ((size_t)(a.part_slot >= 0 ? a.part_slot : sp) * a.H + h) * a.q_rows + a.q_off + q_ld;
+    // this workgroup's keys [kt0, kt1): the whole window, or split sp of a.splits (whole tiles each)
+    const int n_tiles = (n_kv + kF32Keys - 1) / kF32Keys;
+    const int tiles_per_split = (n_tiles + a.splits - 1) / a.splits;
+    const int kt0 = sp * tiles_per_split * kF32Keys;
+    const int kt1 = min(n_kv, (sp + 1) * tiles_per_split * kF32Keys);
 
-    if (n_kv == 0) {
+    if (kt0 >= kt1) {   // empty window, or a split past its end: contributes nothing
         if (q_ok && partial_out) {
             for (int c = g * 64; c < g * 64 + 64; c += 4)
                 *reinterpret_cast<float4 *>(a.part_o + prow * WK_D + c) = float4{0, 0, 0, 0};
@@ -214,14 +219,14 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a, SubTabl
     const float *Kh = reinterpret_cast<const float *>(win.K) + (size_t)h * win.stride * WK_D;
     const float *Vh = reinterpret_cast<const float *>(a.V) + (size_t)h * win.stride * WK_D;
 
-    for (int kt = 0; kt < n_kv; kt += kF32Keys) {
+    for (int kt = kt0; kt < kt1; kt += kF32Keys) {
         __syncthreads();  // previous tile fully consumed
 #pragma unroll
         for (int i = 0; i < (kF32Keys * WK_D / 4) / (kF32Waves * 64); ++i) {
             const int x = tid + i * (kF32Waves * 64);
             const int row = x / (WK_D / 4), c4 = x % (WK_D / 4);
             float4 kv = float4{0, 0, 0, 0}, vv = float4{0, 0, 0, 0};
-            if (kt + row < n_kv) {
+            if (kt + row < kt1) {
                 kv = *reinterpret_cast<const float4 *>(Kh + (size_t)(kt + row) * WK_D + 4 * c4);
                 if (with_o) vv = *reinterpret_cast<const float4 *>(Vh + (size_t)(kt + row) * WK_D + 4 * c4);
             }
@@ -246,7 +251,7 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a, SubTabl
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int key = kt + 8 * (r >> 2) + 4 * g + (r & 3);
-            s[r] = key < n_kv ? s[r] * a.scale_log2 : -INFINITY;
+            s[r] = key < kt1 ? s[r] * a.scale_log2 : -INFINITY;
             m_tile = fmaxf(m_tile, s[r]);
         }
         m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32));
@@ -1006,6 +1011,14 @@ int choose_splits(int items, int n_tiles) {
     return best;
 }
 
+// fp32 kernel: four of its workgroups fit a compute unit, so up to 1024 are resident; the smallest split
+// count that reaches that, at most 16 and leaving at least 4 tiles of 32 keys per split.
+int choose_splits_f32(long long items, int n_tiles) {
+    int s = 1;
+    while (s < kMaxSplits && items * s < 1024 && n_tiles / (s + 1) >= 4) ++s;
+    return s;
+}
+
 size_t split_workspace_bytes(int H, int N_q, int splits) {
     const size_t rows = (size_t)splits * H * N_q;
     return wk::align_up(rows * WK_D * sizeof(float), 256) + wk::align_up(rows * 2 * sizeof(float), 256);
@@ -1095,11 +1108,24 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     if (dtype == WK_F32) {
         const int q_per_wg = kF32Waves * 32;
         a.n_qtiles = (N_q + q_per_wg - 1) / q_per_wg;
-        const long long items = (long long)H * a.n_qtiles;
+        const long long items1 = (long long)H * a.n_qtiles;
+        a.splits = O ? choose_splits_f32(items1, (N_kv + kF32Keys - 1) / kF32Keys) : 1;
+        if (a.splits > 1 && (!workspace || workspace_bytes < split_workspace_bytes(H, N_q, a.splits) ||
+                             reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
+            a.splits = 1;
+        a.part_o = reinterpret_cast<float *>(workspace);
+        a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
+                                              wk::align_up((size_t)a.splits * H * N_q * WK_D * sizeof(float), 256));
+        const long long items = items1 * a.splits;
         if (items + kXcds > 0x7fffffffLL) return WK_ERR_UNSUPPORTED;
         a.per_xcd = (int)((items + kXcds - 1) / kXcds);
         hipLaunchKernelGGL(k_attn_f32<false>, dim3(a.per_xcd * kXcds), dim3(kF32Waves * 64), 0, st, a, SubTable{});
         WK_LAUNCH_CHECK();
+        if (a.splits > 1) {
+            const size_t rows = (size_t)H * N_q;
+            hipLaunchKernelGGL(k_attn_merge<WK_F32>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, a);
+            WK_LAUNCH_CHECK();
+        }
         return WK_OK;
     }
     return launch_bf16<8>(a, workspace, workspace_bytes, st);
@@ -1324,8 +1350,13 @@ extern "C" wk_status wk_attention_in_place(const void *Q, const void *K_native, 
 }
 
 extern "C" size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_t dtype) {
-    if (H < 1 || N_q < 1 || N_kv < 1 || dtype != WK_BF16) return 0;
+    if (H < 1 || N_q < 1 || N_kv < 1 || (dtype != WK_BF16 && dtype != WK_F32)) return 0;
     if ((long long)H * ((N_q + 31) / 32) > 0x7fffffffLL / kMaxSplits) return 0;
+    if (dtype == WK_F32) {
+        const int s = choose_splits_f32((long long)H * ((N_q + kF32Waves * 32 - 1) / (kF32Waves * 32)),
+                                        (N_kv + kF32Keys - 1) / kF32Keys);
+        return s > 1 ? split_workspace_bytes(H, N_q, s) : 0;
+    }
     const int splits = choose_splits(H * ((N_q + 255) / 256), (N_kv + kKeys - 1) / kKeys);
     return splits > 1 ? split_workspace_bytes(H, N_q, splits) : 0;
 }

@@ -139,6 +139,22 @@ def test_argument_validation_of_the_other_calls():
     assert L.wk_chunk_lse(C.byref(sd64), one, 8, 0.0, one, None) == wk.WK_ERR_UNSUPPORTED
     sd0 = wk.wk_store_desc(None, None, None, 0, 0, 2, 128, wk.WK_BF16)
     assert L.wk_chunk_lse(C.byref(sd0), one, 8, 0.0, one, None) == wk.WK_OK      # empty store: nothing to do
+    # attention in place over the store
+    def ip(store=sd, Q=one, Kn=one, Vn=one, n_native=4, stride=4, ids=one, R=2, O=one, N_q=8, scale=0.0):
+        return L.wk_attention_in_place(Q, Kn, Vn, n_native, stride, C.byref(store) if store is not None else None, ids,
+                                       None, R, O, None, N_q, scale, None)
+    assert ip(store=None) == wk.WK_ERR_INVALID_ARG
+    assert ip(Q=None) == wk.WK_ERR_INVALID_ARG
+    assert ip(O=None) == wk.WK_ERR_INVALID_ARG
+    assert ip(Kn=None) == wk.WK_ERR_INVALID_ARG          # native rows announced but not given
+    assert ip(ids=None) == wk.WK_ERR_INVALID_ARG
+    assert ip(R=-1) == wk.WK_ERR_INVALID_ARG
+    assert ip(scale=-1.0) == wk.WK_ERR_INVALID_ARG
+    assert ip(n_native=5) == wk.WK_ERR_SHAPE             # more native rows than the stride
+    assert ip(R=33) == wk.WK_ERR_UNSUPPORTED
+    assert ip(store=sd64) == wk.WK_ERR_UNSUPPORTED
+    assert ip(store=wk.wk_store_desc(256, 256, 256, 4, 10, 2, 128, wk.WK_F32)) == wk.WK_ERR_UNSUPPORTED
+    assert ip(N_q=0) == wk.WK_OK                         # nothing to do
     # prefetch handle: argument checks that need no device
     h = C.c_void_p()
     assert L.wk_prefetch_create(None, 2) == wk.WK_ERR_INVALID_ARG
@@ -172,7 +188,9 @@ def test_argument_validation_of_the_other_calls():
     # key-range splits are only proposed when the plain grid would leave compute units idle
     assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
     assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4
-    assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_F32) == 0
+    assert wk.wk_attention_workspace_bytes(4, 880, 2640, wk.WK_F32) > 4 * 880 * 128 * 4       # the tiny fp32 case splits
+    assert wk.wk_attention_workspace_bytes(40, 4680 * 8, 28080, wk.WK_F32) == 0              # enough workgroups as it is
+    assert wk.wk_attention_workspace_bytes(4, 880, 2640, 7) == 0                              # unknown element type
     assert wk.wk_attention_workspace_bytes(1, 64, 128, wk.WK_BF16) == 0      # too short to split
     # gather
     sd = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 128, wk.WK_BF16)
