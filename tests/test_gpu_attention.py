@@ -136,6 +136,30 @@ def test_more_items_than_compute_units_with_and_without_workspace(H, Nq, Nkv, n_
     _check(Q, K, V, O, lse, N_kv=Nkv if n_dev is None else n_dev, rows=rows)
 
 
+@pytest.mark.parametrize("case", ["overflow", "underflow", "mixed"])
+def test_logits_far_outside_the_range_of_exp2(case):
+    """Rows whose logits reach the hundreds, or lie far below zero for every key, or both kinds of row in one
+    workgroup: the running maximum must keep every exponent in range."""
+    H, Nq, Nkv = 2, 300, 700
+    Q, K, V = _rand(H, Nq, Nkv, torch.bfloat16, seed=77)
+    if case == "overflow":
+        scale = 20.0                                   # logits of several hundred either sign
+    elif case == "underflow":
+        base = torch.randn(H, 1, 128, generator=torch.Generator().manual_seed(5))
+        Q = (base + 0.05 * Q.float()).to(torch.bfloat16)
+        K = (-8.0 * base + 0.05 * K.float()).to(torch.bfloat16)
+        scale = 0.0                                    # default 1/sqrt(d): every logit near -90
+    else:
+        scale = 0.0
+        Q = Q.clone()
+        Q[:, 7] = (Q[:, 7].float() * 300).to(torch.bfloat16)      # one row with huge logits, in two workgroups' tiles
+        Q[:, 290] = (Q[:, 290].float() * 300).to(torch.bfloat16)
+    for split in (False, True):
+        O, lse = _run(Q, K, V, scale=scale, split=split)
+        assert not torch.isnan(O.float()).any() and torch.isfinite(lse).all()
+        _check(Q, K, V, O, lse, scale=None if scale == 0.0 else scale)
+
+
 def test_config0_tiny_fp32_full():
     cfg = ws.get_config(0)
     Q = ws.make_queries(cfg)
