@@ -1024,11 +1024,12 @@ size_t split_workspace_bytes(int H, int N_q, int splits) {
     return wk::align_up(rows * WK_D * sizeof(float), 256) + wk::align_up(rows * 2 * sizeof(float), 256);
 }
 
-// k_attn_bf16 uses more than the default 64 KB of dynamic LDS: raise its limit once per process
-// (not a stream operation, so a first call under graph capture is fine too).
+// k_attn_bf16 uses more than the default 64 KB of dynamic LDS: raise its limit once per device and
+// process (not a stream operation, so a first call under graph capture is fine too).
 wk_status allow_large_lds() {
-    static bool done = false;
-    if (!done) {
+    static std::atomic<uint64_t> done{0};
+    int dev;
+    if (wk::device_needs_setup(done, dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, true, false>),
@@ -1036,7 +1037,7 @@ wk_status allow_large_lds() {
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
             return WK_ERR_HIP;
-        done = true;
+        wk::mark_device(done, dev);
     }
     return WK_OK;
 }

@@ -594,12 +594,13 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
                 hsplits = hsplits > kGemmMaxSplits / asplits ? kGemmMaxSplits / asplits : hsplits;
                 const int splits = asplits * hsplits;
                 float *partial = reinterpret_cast<float *>(wsp + ws.gemm_partial);
-                static bool lds_limit_set = false;   // more than the default 64 KB of dynamic LDS
-                if (!lds_limit_set) {
+                static std::atomic<uint64_t> lds_limit_set{0};   // more than the default 64 KB of dynamic LDS
+                int dev;
+                if (wk::device_needs_setup(lds_limit_set, dev)) {
                     if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_score_gemm),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds) != hipSuccess)
                         return WK_ERR_HIP;
-                    lds_limit_set = true;
+                    wk::mark_device(lds_limit_set, dev);
                 }
                 hipLaunchKernelGGL(k_score_gemm, dim3(cand_tiles, p.G * splits, d->batch), dim3(512), kGemmLds, st, Kc,
                                    A, p, nsq, asplits, hsplits, partial);

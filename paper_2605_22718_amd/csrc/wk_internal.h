@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "wk.h"
 
 #define WK_D 128  // head dimension every kernel is written for
@@ -18,6 +20,17 @@ namespace wk {
 __host__ __device__ inline size_t esize(int dtype) { return dtype == WK_BF16 ? 2 : 4; }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Once per device and process: true if `flags` did not yet have the current device's bit (the caller then
+// does its per-device set-up, e.g. raising a kernel's dynamic-LDS limit, and calls it done with mark_device).
+// A lost race only repeats an idempotent set-up.  Devices beyond 63 always report "not yet".
+inline bool device_needs_setup(const std::atomic<uint64_t> &flags, int &dev) {
+    if (hipGetDevice(&dev) != hipSuccess) dev = -1;
+    return dev < 0 || dev > 63 || !((flags.load(std::memory_order_acquire) >> dev) & 1u);
+}
+inline void mark_device(std::atomic<uint64_t> &flags, int dev) {
+    if (dev >= 0 && dev <= 63) flags.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+}
 
 // wk_gather_window with a cap on the number of workgroups (0 = one per 32 KB work unit)
 wk_status gather_launch(const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids, int32_t R_max,
