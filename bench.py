@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM bytes per wk_attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
 # scaled by what the counter reads for the plain calibration copy (0.500 and 1.000), per workload index;
 # see profiles/hbm_traffic_lingbot_pmc.txt for the commands
-MEASURED_ATTENTION_TRAFFIC = {2: (2 * 648456 + 46800) * 1024}
+MEASURED_ATTENTION_TRAFFIC = {2: (2 * 654284 + 46800) * 1024}
 
 
 def parse():
