@@ -1,6 +1,6 @@
 """GPU parity on seeded random shapes: attention (both element types, with and without workspace, device-side
-window length), attention in place over ragged stores with skipped ids, and compression in every mode, each
-against the oracle.  Shapes are drawn from lists that straddle the tile sizes (32, 64, 256)."""
+window length), attention in place over ragged stores with skipped ids, compression in every mode, the
+frame-causal mask in random window layouts, query-based and pose-based retrieval, each against the oracle.  Shapes are drawn from lists that straddle the tile sizes (32, 64, 256)."""
 import numpy as np
 import pytest
 import torch
@@ -144,3 +144,99 @@ def test_compress_random_modes(seed):
             assert torch.equal(bits(Ko[h].cpu()), bits(K[h][sel])) and torch.equal(bits(Vo[h].cpu()), bits(V[h][sel])), what
         done += 1
     assert done >= 20
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_block_causal_random_layouts(seed):
+    rng = np.random.default_rng(30 + seed)
+    dev = _dev()
+    for it in range(24):
+        H = int(rng.integers(1, 4))
+        frames = int(rng.choice([1, 2, 3, 4, 9, 12]))             # 9 and 12 frames: one launch per frame
+        T = int(rng.choice([1, 7, 32, 33, 100, 256, 300]))
+        Nq = frames * T
+        before, after = int(rng.choice([0, 1, 64, 100, 257])), int(rng.choice([0, 1, 63, 200, 513]))
+        Nkv = before + Nq + after
+        stride = Nkv + int(rng.integers(0, 2))
+        dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+        g = torch.Generator().manual_seed(3000 * seed + it)
+        Q, K, V = _rand((H, Nq, 128), dtype, g), _rand((H, stride, 128), dtype, g), _rand((H, stride, 128), dtype, g)
+        wsb = torch.empty(wk.wk_attention_block_causal_workspace_bytes(H, Nq), dtype=torch.uint8, device=dev)
+        O = torch.full(Q.shape, float("nan"), dtype=dtype, device=dev)
+        lse = torch.full((H, Nq), float("nan"), dtype=torch.float32, device=dev)
+        what = f"case {it}: H={H} frames={frames} T={T} before={before} after={after} {dtype}"
+        wk.wk_attention_block_causal(Q.to(dev), K.to(dev), V.to(dev), O, before, T, wsb, lse=lse, N_kv=Nkv)
+        torch.cuda.synchronize()
+        ref, ref_lse = oracle.attention_block_causal(Q, K, V, before, T, N_kv=Nkv, want_lse=True)
+        mx, mean = attention_errors(O, ref)
+        tol = (2e-2, 2e-3) if dtype == torch.bfloat16 else (2e-5, 2e-6)
+        assert mx <= tol[0] and mean <= tol[1], (what, mx, mean)
+        el = np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max()
+        assert el <= (2e-2 if dtype == torch.bfloat16 else 1e-4), (what, el)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_query_retrieval_random_stores(seed):
+    rng = np.random.default_rng(40 + seed)
+    dev = _dev()
+    for it in range(16):
+        H = int(rng.integers(1, 4))
+        Nq = int(rng.choice([1, 33, 256, 300]))
+        M = int(rng.integers(1, 9))
+        lens = [int(rng.choice([1, 5, 63, 64, 65, 128, 200])) for _ in range(M)]
+        R = int(rng.integers(1, 10))
+        dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+        g = torch.Generator().manual_seed(4000 * seed + it)
+        Q = _rand((H, Nq, 128), dtype, g)
+        ks = [_rand((H, n, 128), dtype, g) for n in lens]
+        store = wk.Store([k.to(dev) for k in ks], [k.to(dev) for k in ks])
+        lse = torch.full((M, H, Nq), float("nan"), dtype=torch.float32, device=dev)
+        what = f"case {it}: H={H} Nq={Nq} lens={lens} R={R} {dtype}"
+        wk.wk_chunk_lse(store.desc, Q.to(dev), lse)
+        wsb = torch.empty(wk.wk_score_chunks_query_workspace_bytes(M, H * Nq), dtype=torch.uint8, device=dev)
+        ids = torch.full((R,), -7, dtype=torch.int32, device=dev)
+        mass = torch.zeros(R, dtype=torch.float64, device=dev)
+        nf = torch.zeros(1, dtype=torch.int32, device=dev)
+        wk.wk_score_chunks_query(lse, M, H * Nq, R, ids, mass, nf, wsb)
+        torch.cuda.synchronize()
+        oids, _, oall = oracle.score_chunks_query(Q, ks, R)
+        n = int(nf.item())
+        assert n == min(R, M), what
+        gm = wsb[: M * 8].view(torch.float64).cpu().numpy()
+        tolm = 5e-3 if dtype == torch.bfloat16 else 1e-5        # masses are sums of exp(lse differences) of fp32 lse
+        assert np.abs(gm - oall).max() <= tolm, (what, np.abs(gm - oall).max())
+        gi = ids.cpu().numpy()
+        for a_, b_ in zip(gi[:n], oids):                        # same ids, except between masses that tie
+            assert a_ == b_ or abs(oall[a_] - oall[b_]) <= 2 * tolm, (what, gi, oids)
+        assert (gi[n:] == -1).all(), what
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_pose_retrieval_random_tables(seed):
+    rng = np.random.default_rng(50 + seed)
+    dev = _dev()
+    for it in range(30):
+        M = int(rng.choice([0, 1, 2, 5, 16, 100, 1000]))
+        R = int(rng.integers(1, 20))
+        mode = int(rng.integers(0, 3))
+        poses = np.zeros((max(M, 1), 5), np.float32)
+        poses[:, :3] = rng.normal(0, 5, (max(M, 1), 3))
+        poses[:, 3] = rng.uniform(-4, 4, max(M, 1))
+        poses[:, 4] = rng.uniform(-1, 1, max(M, 1))
+        if M > 3 and rng.random() < 0.5:
+            poses[M // 2] = poses[0]                            # an exact duplicate: a tie, lower id first
+        cur = poses[0] + rng.normal(0, 0.1, 5).astype(np.float32)
+        ids = torch.full((R,), -7, dtype=torch.int32, device=dev)
+        dist = torch.zeros(R, dtype=torch.float64, device=dev)
+        nf = torch.zeros(1, dtype=torch.int32, device=dev)
+        what = f"case {it}: M={M} R={R} mode={mode}"
+        wk.wk_score_chunks(torch.from_numpy(poses).to(dev), M, cur, mode, R, ids, dist, nf)
+        torch.cuda.synchronize()
+        oids, od, oall = oracle.score_chunks(poses[:M], cur, R, mode)
+        n = int(nf.item())
+        assert n == min(R, M), what
+        gi, gd = ids.cpu().numpy()[:n], dist.cpu().numpy()[:n]
+        if n:
+            assert np.abs(gd - od).max() <= 1e-9, (what, np.abs(gd - od).max())
+        for a_, b_ in zip(gi, oids):
+            assert a_ == b_ or abs(oall[a_] - oall[b_]) <= 1e-6, (what, gi, oids)
