@@ -9,6 +9,7 @@
 // are fp32 (bf16 products are exact in fp32), everything across lanes and heads is fp64, so the
 // scores agree with an fp64 evaluation of the double sum to ~1e-9 absolute.
 #include <cmath>
+#include <type_traits>
 
 #include "wk_internal.h"
 
@@ -286,25 +287,43 @@ __global__ __launch_bounds__(512, 2) void k_score_gemm(const char *__restrict__ 
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
-        if (n_steps > 0) issue(0, 0);
-        for (int step = 0; step < n_steps; ++step) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the step's tiles has landed
-            __syncthreads();                      // everyone's has, and the other stage is free again
-            if (step + 1 < n_steps) issue(step + 1, (step + 1) & 1);
-            const int off = (step & 1) * kGemmStage;
+        // 32-row groups of this wave's 128 anchors that hold at least one anchor below T: all 4 except in
+        // the last anchor block, where the groups of pure padding are skipped (their weights are 0 anyway)
+        const int rows_left = p.T - (ab * kGemmTile + 128 * wa);
+        const int mb_valid = rows_left >= 128 ? 4 : (rows_left <= 0 ? 0 : (rows_left + 31) / 32);
+        auto contract = [&](auto mv_tag) {
+            constexpr int MV = decltype(mv_tag)::value;
+            for (int step = 0; step < n_steps; ++step) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the step's tiles has landed
+                __syncthreads();                      // everyone's has, and the other stage is free again
+                if (step + 1 < n_steps) issue(step + 1, (step + 1) & 1);
+                const int off = (step & 1) * kGemmStage;
+                if constexpr (MV > 0) {
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                bf16x8 fa[4], fb[2];
+                    for (int st = 0; st < 4; ++st) {
+                        bf16x8 fa[MV], fb[2];
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb) fa[mb] = *reinterpret_cast<const bf16x8 *>(a_rd[st] + off + mb * 4096);
+                        for (int mb = 0; mb < MV; ++mb)
+                            fa[mb] = *reinterpret_cast<const bf16x8 *>(a_rd[st] + off + mb * 4096);
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb) fb[nb] = *reinterpret_cast<const bf16x8 *>(b_rd[st] + off + nb * 4096);
+                        for (int nb = 0; nb < 2; ++nb)
+                            fb[nb] = *reinterpret_cast<const bf16x8 *>(b_rd[st] + off + nb * 4096);
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
+                        for (int mb = 0; mb < MV; ++mb)
 #pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[nb], acc[mb][nb], 0, 0, 0);
+                            for (int nb = 0; nb < 2; ++nb)
+                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[nb], acc[mb][nb], 0, 0, 0);
+                    }
+                }
             }
+        };
+        if (n_steps > 0) issue(0, 0);
+        switch (mb_valid) {   // wave-uniform; every variant passes the same barriers
+        case 4: contract(std::integral_constant<int, 4>{}); break;
+        case 3: contract(std::integral_constant<int, 3>{}); break;
+        case 2: contract(std::integral_constant<int, 2>{}); break;
+        case 1: contract(std::integral_constant<int, 1>{}); break;
+        default: contract(std::integral_constant<int, 0>{}); break;
         }
         // fold the block in: accumulator register r of block mb is anchor 128*wa + 32*mb + 8*(r/4) + 4*gh + r%4
         // (an empty head range has passed no barrier since the weights were written, and has nothing to add)
