@@ -179,3 +179,41 @@ def test_chunk_lse_against_oracle_with_empty_and_pinned_chunks(index):
             continue
         _, ref = oracle.attention(Q, K, K, want_lse=True)
         assert np.abs(got[c] - ref).max() <= (1e-4 if Q.dtype == torch.float32 else 2e-2), c
+
+
+def test_chunk_lse_and_masses_at_the_lingbot_index_size_sampled():
+    """The index the bench times: anchor-frame keys (1,560 per chunk) of 120 stored chunks, 40 heads, 4,680
+    queries.  Sampled (chunk, query row) entries of the log-sum-exp against the oracle on all heads, and the masses
+    and ids of wk_score_chunks_query against a softmax over the GPU's own log-sum-exps taken in fp64."""
+    d = dev()
+    cfg = ws.get_config(2)
+    M, n_anchor = cfg.M, cfg.T
+    Q = ws.make_queries(cfg, d)
+    keys = torch.empty((M, cfg.H, n_anchor, cfg.d), dtype=torch.bfloat16, device=d)
+    for c in range(M):
+        keys[c] = ws.make_native(cfg.with_(index=200 + c), d, n_rows=n_anchor)[0]
+    store = wk.Store([keys[c] for c in range(M)], [keys[c] for c in range(M)], d)
+    lse = torch.full((M, cfg.H, cfg.N_q), float("nan"), dtype=torch.float32, device=d)
+    wk.wk_chunk_lse(store.desc, Q, lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(lse).all()
+    rng = np.random.default_rng(7)
+    rows = sorted(set([0, 255, 256, cfg.N_q - 1] + rng.integers(0, cfg.N_q, 8).tolist()))
+    Qc = Q.cpu()
+    for c in [0, 1, 57, M - 1]:
+        Kc = keys[c].cpu()
+        _, ref = oracle.attention(Qc, Kc, Kc, rows=rows, want_lse=True)
+        got = lse[c][:, rows].cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref).max() <= 2e-2, c
+    n_rows = cfg.H * cfg.N_q
+    wsb = torch.empty(wk.wk_score_chunks_query_workspace_bytes(M, n_rows), dtype=torch.uint8, device=d)
+    ids = torch.full((cfg.R,), -7, dtype=torch.int32, device=d)
+    mass = torch.zeros(cfg.R, dtype=torch.float64, device=d)
+    nf = torch.zeros(1, dtype=torch.int32, device=d)
+    wk.wk_score_chunks_query(lse, M, n_rows, cfg.R, ids, mass, nf, wsb)
+    torch.cuda.synchronize()
+    all_mass = wsb[: M * 8].view(torch.float64).cpu().numpy()
+    expect = torch.softmax(lse.view(M, n_rows).double(), 0).mean(1).cpu().numpy()
+    np.testing.assert_allclose(all_mass, expect, rtol=1e-9)
+    assert abs(all_mass.sum() - 1.0) < 1e-9 and int(nf.item()) == cfg.R
+    np.testing.assert_array_equal(ids.cpu().numpy(), np.lexsort((np.arange(M), -expect))[: cfg.R])
