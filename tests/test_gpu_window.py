@@ -157,3 +157,41 @@ def test_rolling_generation_loop_through_every_entry_point():
         mx, mean = attention_errors(O, oracle.attention(Q.cpu(), oKw, oVw, N_kv=o_n))
         assert mx <= ATT_MAX_ABS_BF16 and mean <= ATT_MEAN_ABS_BF16, (c, mx, mean)
     assert len(o_store_k) == n_chunks - 3 and p.M == n_chunks - 3      # all but the sink chunk and the two in the ring
+
+
+def test_slot_refresh_at_the_lingbot_window_size():
+    """Config 2 at full size: 8 slots of 2,340 rows x 40 heads behind 9,360 native rows.  First fill, then a
+    request that keeps five chunks and brings three new ones: only those three are copied, every slot holds its
+    chunk byte for byte, the native rows stay as they were."""
+    d = dev()
+    cfg = ws.get_config(2)
+    n_out, _ = wk.wk_keep_count(cfg.rho, cfg.ratio_kind, cfg.anchor_mode, cfg.F, cfg.T)
+    M, R = 12, cfg.R
+    Ks, Vs = [], []
+    for c in range(M):
+        k, v = ws.make_native(cfg.with_(index=300 + c), d, n_rows=n_out)
+        Ks.append(k), Vs.append(v)
+    store = wk.Store(Ks, Vs, d)
+    cap = cfg.n_native + R * n_out
+    Kn, Vn = ws.make_native(cfg, d)
+    Kw = torch.zeros((cfg.H, cap, cfg.d), dtype=torch.bfloat16, device=d)
+    Vw = torch.zeros_like(Kw)
+    Kw[:, :cfg.n_native], Vw[:, :cfg.n_native] = Kn, Vn
+    slot_ids = torch.full((R,), -1, dtype=torch.int32, device=d)
+    n_win = torch.zeros(1, dtype=torch.int32, device=d)
+    n_f = torch.zeros(1, dtype=torch.int32, device=d)
+    wsb = torch.empty(wk.wk_window_update_workspace_bytes(R), dtype=torch.uint8, device=d)
+    model = [-1] * R
+    for req, expect_fetched in (([0, 1, 2, 3, 4, 5, 6, 7], 8), ([7, 9, 1, 3, 10, 5, 11, 0], 3)):
+        ids = torch.tensor(req, dtype=torch.int32, device=d)
+        n_ids = torch.tensor([len(req)], dtype=torch.int32, device=d)
+        wk.wk_window_update(store.desc, ids, n_ids, R, n_out, slot_ids, cfg.n_native, Kw, Vw, cap, n_win, n_f, wsb)
+        torch.cuda.synchronize()
+        model, fetched = update_slots(model, req, R, lambda i: 0 <= i < M)
+        assert slot_ids.cpu().tolist() == model
+        assert int(n_f.item()) == len(fetched) == expect_fetched
+        assert int(n_win.item()) == cap
+        for s, c in enumerate(model):
+            r0 = cfg.n_native + s * n_out
+            assert torch.equal(bits(Kw[:, r0:r0 + n_out]), bits(Ks[c])) and torch.equal(bits(Vw[:, r0:r0 + n_out]), bits(Vs[c])), s
+        assert torch.equal(bits(Kw[:, :cfg.n_native]), bits(Kn)) and torch.equal(bits(Vw[:, :cfg.n_native]), bits(Vn))
