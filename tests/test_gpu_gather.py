@@ -76,28 +76,36 @@ def test_no_native_rows_and_no_retrieval():
     assert n_win == 33 and torch.equal(bits(Kw), bits(Kn)) and torch.equal(bits(Vw), bits(Vn))
 
 
-def test_config1_sized_gather():
-    cfg = ws.get_config(1)
+@pytest.mark.parametrize("ci,order", [(1, (4, 0, 5, 2)), (2, (9, 4, 0, 5, 2, 11, 7, 1))])
+def test_config_sized_gather(ci, order):
+    """Configs 1 and 2 at full size from an HBM store, in the launch the bench times (ids on the device)."""
+    cfg = ws.get_config(ci)
     d = dev()
-    n_out = 1320
-    ks = [ws.make_native(cfg.with_(index=70 + c), d, n_rows=n_out) for c in range(6)]
+    n_out, _ = wk.wk_keep_count(cfg.rho, cfg.ratio_kind, cfg.anchor_mode, cfg.F, cfg.T)
+    ks = [ws.make_native(cfg.with_(index=70 + c), d, n_rows=n_out) for c in range(12)]
     store = wk.Store([k for k, _ in ks], [v for _, v in ks])
     Kn, Vn = ws.make_native(cfg, d)
     cap = cfg.n_native + cfg.R * n_out
     Kw = torch.zeros((cfg.H, cap, cfg.d), dtype=torch.bfloat16, device=d)
     Vw = torch.zeros_like(Kw)
-    ids = torch.tensor([4, 0, 5, 2], dtype=torch.int32, device=d)
+    ids = torch.tensor(order, dtype=torch.int32, device=d)
     n_win = torch.zeros(1, dtype=torch.int32, device=d)
-    wk.wk_gather_window(store.desc, ids, None, 4, Kn, Vn, cfg.n_native, Kw, Vw, cap, n_win)
+    wk.wk_gather_window(store.desc, ids, None, cfg.R, Kn, Vn, cfg.n_native, Kw, Vw, cap, n_win)
     torch.cuda.synchronize()
-    assert int(n_win.item()) == cap == 10560
-    expect_k = torch.cat([Kn] + [ks[i][0] for i in (4, 0, 5, 2)], 1)
-    expect_v = torch.cat([Vn] + [ks[i][1] for i in (4, 0, 5, 2)], 1)
+    assert int(n_win.item()) == cap == (10560 if ci == 1 else 28080)
+    expect_k = torch.cat([Kn] + [ks[i][0] for i in order], 1)
+    expect_v = torch.cat([Vn] + [ks[i][1] for i in order], 1)
     assert torch.equal(bits(Kw), bits(expect_k)) and torch.equal(bits(Vw), bits(expect_v))
     # byte-exact against the oracle on one head's slice (the oracle copies on the CPU)
-    oK, oV, _ = oracle.gather([k[:1].cpu() for k, _ in ks], [v[:1].cpu() for _, v in ks], [4, 0, 5, 2],
+    oK, oV, _ = oracle.gather([k[:1].cpu() for k, _ in ks], [v[:1].cpu() for _, v in ks], list(order),
                               Kn[:1].cpu(), Vn[:1].cpu(), cap)
     assert torch.equal(bits(Kw[:1].cpu()), bits(oK)) and torch.equal(bits(Vw[:1].cpu()), bits(oV))
+    # native rows already in place: only the retrieved chunks move, same window
+    Kw2, Vw2 = torch.zeros_like(Kw), torch.zeros_like(Vw)
+    Kw2[:, :cfg.n_native], Vw2[:, :cfg.n_native] = Kn, Vn
+    wk.wk_gather_window(store.desc, ids, None, cfg.R, None, None, cfg.n_native, Kw2, Vw2, cap, n_win)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(Kw2), bits(expect_k)) and torch.equal(bits(Vw2), bits(expect_v))
 
 
 def test_calibration_copy_is_exact():
