@@ -263,3 +263,65 @@ def test_window_plan_matches_the_rolling_window_simulation():
     assert upd(ws=None) == wk.WK_ERR_WORKSPACE
     assert upd(ws_bytes=8) == wk.WK_ERR_WORKSPACE
     assert wk.wk_window_update_workspace_bytes(1025) == 0 and wk.wk_window_update_workspace_bytes(6) >= 256 + 48
+
+
+C_PROGRAM = r"""
+#include <stdio.h>
+#include <stddef.h>
+#include <string.h>
+#include "wk.h"
+int main(void) {
+    int32_t n_out = 0, n_keep = 0;
+    if (wk_keep_count(0.25f, WK_RATIO_NONANCHOR, WK_ANCHOR_FIRST_FRAME, 3, 880, &n_out, &n_keep) != WK_OK) return 1;
+    printf("keep %d %d\n", (int)n_out, (int)n_keep);
+    printf("status %s\n", wk_status_string(WK_ERR_WORKSPACE));
+    printf("sizes %d %d %d %d\n", (int)sizeof(wk_compress_desc), (int)sizeof(wk_store_desc), (int)sizeof(wk_window_desc),
+           (int)sizeof(wk_window_step));
+    printf("offsets %d %d %d\n", (int)offsetof(wk_store_desc, M), (int)offsetof(wk_window_step, evict_chunk),
+           (int)offsetof(wk_window_step, win_capacity));
+    wk_window_desc w = {1560, 3, 1, 1, 6, 2340};
+    for (long long c = 0; c < 6; ++c) {
+        wk_window_step s;
+        if (wk_window_plan(&w, c, &s) != WK_OK) return 2;
+        printf("plan %lld %d %d %d %d %d %d %lld %d %d %d\n", c, (int)s.denoise_row0, (int)s.denoise_rows, (int)s.n_native,
+               (int)s.evict, (int)s.evict_row0, (int)s.store_id, (long long)s.evict_chunk, (int)s.M, (int)s.retrieved_row0,
+               (int)s.win_capacity);
+    }
+    /* argument errors come back as status codes, before anything touches a device */
+    if (wk_attention(NULL, NULL, NULL, NULL, NULL, 1, 1, 1, 128, 1, WK_BF16, 0.f, NULL, NULL, 0, NULL) != WK_ERR_INVALID_ARG)
+        return 3;
+    return 0;
+}
+"""
+
+
+def test_header_is_c99_and_a_c_program_sees_what_the_binding_sees(tmp_path):
+    """include/wk.h compiles as strict C99; a C program linked against libwk.so gets the same counts, structure
+    layouts and window plans as the ctypes binding."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "abi.c"
+    src.write_text(C_PROGRAM)
+    libdir = os.path.dirname(wk.lib()._name)
+    exe = tmp_path / "abi"
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+           "-L", libdir, "-lwk", "-Wl,-rpath," + libdir, "-Wl,-rpath-link,/opt/rocm/lib", "-o", str(exe)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    lines = r.stdout.split("\n")
+    assert lines[0] == "keep 1320 440"
+    assert lines[1] == "status " + wk.status_string(wk.WK_ERR_WORKSPACE)
+    assert lines[2] == "sizes %d %d %d %d" % (C.sizeof(wk.wk_compress_desc), C.sizeof(wk.wk_store_desc),
+                                               C.sizeof(wk.wk_window_desc), C.sizeof(wk.wk_window_step))
+    assert lines[3] == "offsets %d %d %d" % (wk.wk_store_desc.M.offset, wk.wk_window_step.evict_chunk.offset,
+                                             wk.wk_window_step.win_capacity.offset)
+    w = wk.wk_window_desc(1560, 3, 1, 1, 6, 2340)
+    for c in range(6):
+        s = wk.wk_window_plan(w, c)
+        assert lines[4 + c] == "plan %d %d %d %d %d %d %d %d %d %d %d" % (
+            c, s.denoise_row0, s.denoise_rows, s.n_native, s.evict, s.evict_row0, s.store_id, s.evict_chunk, s.M,
+            s.retrieved_row0, s.win_capacity)
