@@ -306,7 +306,8 @@ __global__ __launch_bounds__(kF32Waves * 64) void k_attn_f32(AttnArgs a, SubTabl
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16: v_mfma_f32_32x32x16_bf16, 8 waves x 32 queries per workgroup, 64-key tiles.
+// bf16: v_mfma_f32_32x32x16_bf16, 8 waves x 32 queries per workgroup (4 waves x 32 for small grids),
+// 64-key tiles.
 //
 // K and V tiles go from global memory straight into a 4-deep LDS ring (global_load_lds, no
 // register staging), K tiles four and V tiles three ahead of the step that loads them, which
@@ -352,7 +353,10 @@ __device__ inline const char *uniform_ptr(const char *p) {
 
 template <int WAVES, bool MULTI, bool IN_PLACE>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTable sub) {
-    static_assert(WAVES == 8, "tile loads are laid out for 8 waves");
+    static_assert(WAVES == 8 || WAVES == 4, "8 or 4 waves of 32 queries");
+    constexpr int NB = 16 / WAVES;     // 1 KB blocks of a tile that a wave loads
+    // s_waitcnt vmcnt(4 * NB), everything else unconstrained: all but the last four tile shares have landed
+    constexpr int kWaitTwoSteps = NB == 2 ? 0x0F78 : 0x4F70;
     static_assert(!(MULTI && IN_PLACE), "a table of launches over one window array only");
     extern __shared__ __attribute__((aligned(256))) char smem[];
     int c, h, qt, sp;
@@ -463,14 +467,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
             v_rd[blk] = smem + kVRing + (4 * g + (p >> 2)) * 256 +
                         ((4 * (blk ^ (p >> 2)) + 2 * (u & 1) + ((p & 3) >> 1)) << 4) + 8 * (p & 1);
     }
-    // tile loads: wave w fills 1 KB blocks 2*w and 2*w+1 of the K tile and of the V tile; lane l of
-    // a block lands in 16-byte slot l = (row r = l >> 4 of the block, slot p = l & 15)
-    unsigned k_src[2], v_src[2];
+    // tile loads: wave w fills 1 KB blocks NB*w .. NB*w + NB-1 of the K tile and of the V tile; lane l
+    // of a block lands in 16-byte slot l = (row r = l >> 4 of the block, slot p = l & 15)
+    unsigned k_src[NB], v_src[NB];
     {
         const int r = lane >> 4, p = lane & 15;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int R = 4 * (2 * wave + i) + r;
+        for (int i = 0; i < NB; ++i) {
+            const int R = 4 * (NB * wave + i) + r;
             k_src[i] = R * 256 + ((p ^ (R & 15)) << 4);
             v_src[i] = R * 256 + ((p ^ (r << 2)) << 4);
         }
@@ -478,9 +482,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     const char *Kh = win.K + (size_t)h * win.stride * 256;
     const char *Vh = a.V + (size_t)h * win.stride * 256;
     const unsigned last_off = (unsigned)(n_kv - 1) * 256u;
-    char *const dma_dst = smem + wave * 2048;   // + slot*16384 (+ kVRing) + i*1024
+    char *const dma_dst = smem + wave * (NB * 1024);   // + slot*16384 (+ kVRing) + i*1024
 
-    // Loads: 2 per wave for a K tile, 2 for a V tile (rel = tile index relative to t0).  Rows past the
+    // Loads: NB per wave for a K tile, NB for a V tile (rel = tile index relative to t0).  Rows past the
     // window clamp to the last key; those keys are masked (weight exactly 0) before they can contribute.
     // IN_PLACE: one cursor walks the segment list in steps of a tile, at the K loads, which lead
     // everything else.  What later stages need of a tile is kept from the moment its K tile was requested:
@@ -501,16 +505,16 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         }
     }
     // one tile: rows past the segment's end clamp to its last row (those keys are masked when consumed)
-    auto issue_at = [&](const char *base, int row, int len, const unsigned (&src)[2], char *dst) {
+    auto issue_at = [&](const char *base, int row, int len, const unsigned (&src)[NB], char *dst) {
         const unsigned t_off = (unsigned)row * 256u;
         if (row + kKeys <= len) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < NB; ++i)
                 __builtin_amdgcn_global_load_lds(WK_GLB(base + (t_off + src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
         } else {
             const unsigned seg_last = (unsigned)(len - 1) * 256u;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < NB; ++i) {
                 const unsigned o = min(t_off + src[i], seg_last + (src[i] & 255u));
                 __builtin_amdgcn_global_load_lds(WK_GLB(base + o), WK_LDS(dst + i * 1024), 16, 0, 0);
             }
@@ -543,11 +547,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         }
         if ((t0 + rel + 1) * kKeys <= n_kv) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < NB; ++i)
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + (t_off + k_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
         } else {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < NB; ++i) {
                 const unsigned ko = min(t_off + k_src[i], last_off + (k_src[i] & 255u));
                 __builtin_amdgcn_global_load_lds(WK_GLB(Kh + ko), WK_LDS(dst + i * 1024), 16, 0, 0);
             }
@@ -562,11 +566,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         }
         if ((t0 + rel + 1) * kKeys <= n_kv) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < NB; ++i)
                 __builtin_amdgcn_global_load_lds(WK_GLB(Vh + (t_off + v_src[i])), WK_LDS(dst + i * 1024), 16, 0, 0);
         } else {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < NB; ++i) {
                 const unsigned vo = min(t_off + v_src[i], last_off + (v_src[i] & 255u));
                 __builtin_amdgcn_global_load_lds(WK_GLB(Vh + vo), WK_LDS(dst + i * 1024), 16, 0, 0);
             }
@@ -678,7 +682,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     issue_v(1, (sh + 1) & 3);
     issue_k(3, (sh + 3) & 3);
     issue_v(2, (sh + 2) & 3);
-    __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): K tiles 0, 1 and V tile 0 of this wave have landed
+    __builtin_amdgcn_s_waitcnt(kWaitTwoSteps);   // K tiles 0, 1 and V tile 0 of this wave have landed
     __syncthreads();
     if (qt * (WAVES * 32) + wave * 32 >= a.N_q) {
         // A wave whose 32 queries all lie past N_q (last query tile of a head): it keeps loading its
@@ -688,7 +692,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         for (int j = 0; j < n_steps; ++j) {
             issue_k(j + 4, (j + sh) & 3);
             issue_v(j + 3, (j + sh + 3) & 3);
-            __builtin_amdgcn_s_waitcnt(0x0F78);
+            __builtin_amdgcn_s_waitcnt(kWaitTwoSteps);
             __syncthreads();
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -721,7 +725,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         if constexpr (IN_PLACE) mask_segment_tail(s_next);
         accumulate_pv(POS * kTileBytes, pb);
         mt = tile_max(s_next);
-        __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): all but the loads of this step and the one before have landed
+        __builtin_amdgcn_s_waitcnt(kWaitTwoSteps);   // all but the loads of this step and the one before have landed
         __syncthreads();
     };
     using P0 = std::integral_constant<int, 0>;
@@ -1011,6 +1015,35 @@ int choose_splits(int items, int n_tiles) {
     return best;
 }
 
+// How a bf16 launch is laid out, chosen by a cost model in units of one 64-key step of a 256-query
+// workgroup (measured: a 128-query workgroup, one wave per SIMD, takes 0.69 of that per step; a workgroup's
+// fill and drain cost about 4 steps; the merge of s partial results costs about 6 steps plus its traffic):
+//   waves = 8, splits = 1   one workgroup per (head, 256 queries): large grids
+//   waves = 8, splits > 1   the key range split over workgroups and merged: small grids, long windows
+//   waves = 4               one workgroup per (head, 128 queries), twice as many of them: small grids, short
+//                           windows, or no workspace for partial results
+struct LaunchPlan { int waves, splits; };
+
+LaunchPlan plan_bf16(int H, int N_q, int N_kv, bool workspace_ok) {
+    const int n_tiles = (N_kv + 63) / 64;
+    const long long items8 = (long long)H * ((N_q + 255) / 256), items4 = (long long)H * ((N_q + 127) / 128);
+    auto rounds = [](long long wgs) { return (double)((wgs + 255) / 256); };
+    const double plain8 = rounds(items8) * (n_tiles + 4);
+    const double plain4 = rounds(items4) * (n_tiles + 4) * 0.69;
+    LaunchPlan best{8, 1};
+    double best_cost = plain8;
+    if (plain4 < 0.97 * best_cost) { best = LaunchPlan{4, 1}; best_cost = plain4; }
+    if (workspace_ok && items8 <= 0x7fffffff / kMaxSplits) {
+        const int s = choose_splits((int)items8, n_tiles);
+        if (s > 1) {
+            const double merge = 6.0 + 2.0 * s * H * (double)N_q * 516.0 / 5e12 / 1.76e-6;
+            const double split8 = rounds(items8 * s) * ((double)n_tiles / s + 4) + merge;
+            if (split8 < 0.97 * best_cost) best = LaunchPlan{8, s};
+        }
+    }
+    return best;
+}
+
 // fp32 kernel: four of its workgroups fit a compute unit, so up to 1024 are resident; the smallest split
 // count that reaches that, at most 16 and leaving at least 4 tiles of 32 keys per split.
 int choose_splits_f32(long long items, int n_tiles) {
@@ -1032,6 +1065,8 @@ wk_status allow_large_lds() {
     if (wk::device_needs_setup(done, dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<4, false, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, true, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, true>),
@@ -1043,13 +1078,10 @@ wk_status allow_large_lds() {
 }
 
 template <int WAVES>
-wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipStream_t st) {
+wk_status launch_bf16(AttnArgs a, int splits, void *workspace, hipStream_t st) {
     const int q_per_wg = WAVES * 32;
     a.n_qtiles = (a.N_q + q_per_wg - 1) / q_per_wg;
-    a.splits = a.O && a.n_chunks == 0 ? choose_splits(a.H * a.n_qtiles, (a.N_kv + kKeys - 1) / kKeys) : 1;
-    if (a.splits > 1 && (!workspace || workspace_bytes < split_workspace_bytes(a.H, a.N_q, a.splits) ||
-                         reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
-        a.splits = 1;   // no room for partial results: one workgroup walks the whole window
+    a.splits = splits;
     a.part_o = reinterpret_cast<float *>(workspace);
     a.part_ml = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) +
                                           wk::align_up((size_t)a.splits * a.H * a.N_q * WK_D * sizeof(float), 256));
@@ -1058,11 +1090,13 @@ wk_status launch_bf16(AttnArgs a, void *workspace, size_t workspace_bytes, hipSt
     a.per_xcd = (int)((items + kXcds - 1) / kXcds);
     const wk_status lds_rc = allow_large_lds();
     if (lds_rc != WK_OK) return lds_rc;
-    if (a.O)
+    if (a.O) {
         hipLaunchKernelGGL((k_attn_bf16<WAVES, false, false>), dim3(a.per_xcd * kXcds), dim3(WAVES * 64), kSmemBytes, st, a,
                            SubTable{});
-    else
+    } else {
+        if (WAVES != 8) return WK_ERR_UNSUPPORTED;   // the log-sum-exp kernel is laid out for 256-query workgroups
         hipLaunchKernelGGL(k_lse_bf16, dim3(a.per_xcd * kXcds), dim3(512), kVRing, st, a);
+    }
     WK_LAUNCH_CHECK();
     if (a.splits > 1) {
         const size_t rows = (size_t)a.H * a.N_q;
@@ -1129,7 +1163,13 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
         }
         return WK_OK;
     }
-    return launch_bf16<8>(a, workspace, workspace_bytes, st);
+    if (!O) return launch_bf16<8>(a, 1, nullptr, st);   // log-sum-exp only
+    const bool ws_aligned = workspace && reinterpret_cast<uintptr_t>(workspace) % 256 == 0;
+    // the plan with a workspace, if the one given is big enough for it; otherwise the best plan without
+    LaunchPlan plan = plan_bf16(H, N_q, N_kv, ws_aligned);
+    if (plan.splits > 1 && workspace_bytes < split_workspace_bytes(H, N_q, plan.splits))
+        plan = plan_bf16(H, N_q, N_kv, false);
+    return plan.waves == 8 ? launch_bf16<8>(a, plan.splits, workspace, st) : launch_bf16<4>(a, 1, nullptr, st);
 }
 
 namespace {
@@ -1300,7 +1340,7 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
         WK_LAUNCH_CHECK();
         return WK_OK;
     }
-    return launch_bf16<8>(a, nullptr, 0, st);
+    return launch_bf16<8>(a, 1, nullptr, st);
 }
 
 extern "C" wk_status wk_attention_in_place(const void *Q, const void *K_native, const void *V_native,
@@ -1358,8 +1398,8 @@ extern "C" size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N
                                         (N_kv + kF32Keys - 1) / kF32Keys);
         return s > 1 ? split_workspace_bytes(H, N_q, s) : 0;
     }
-    const int splits = choose_splits(H * ((N_q + 255) / 256), (N_kv + kKeys - 1) / kKeys);
-    return splits > 1 ? split_workspace_bytes(H, N_q, splits) : 0;
+    const LaunchPlan plan = plan_bf16(H, N_q, N_kv, true);
+    return plan.splits > 1 ? split_workspace_bytes(H, N_q, plan.splits) : 0;
 }
 
 extern "C" const char *wk_status_string(wk_status s) {

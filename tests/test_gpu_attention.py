@@ -108,7 +108,7 @@ def test_normalisation_and_special_cases(dtype):
 def test_split_key_range_matches_oracle_and_unsplit(H, Nq, Nkv, n_dev):
     """Few workgroups and a long window: the key range is split over workgroups and merged."""
     Q, K, V = _rand(H, Nq, Nkv, torch.bfloat16, seed=Nkv + Nq)
-    assert wk.wk_attention_workspace_bytes(H, Nq, Nkv, wk.WK_BF16) > 0
+    assert (wk.wk_attention_workspace_bytes(H, Nq, Nkv, wk.WK_BF16) > 0) == (Nkv >= 2048)   # shorter: 128-query workgroups
     O, lse = _run(Q, K, V, n_kv_dev=n_dev)
     O1, lse1 = _run(Q, K, V, n_kv_dev=n_dev, split=False)
     if n_dev == 0:
@@ -182,8 +182,8 @@ def test_full_size_configs_sampled_rows(ci, n_random):
     K, V = ws.make_native(cfg, d, n_rows=N_kv)
     O = torch.empty_like(Q)
     lse = torch.empty(Q.shape[:2], dtype=torch.float32, device=d)
-    wsb = _workspace(cfg.H, cfg.N_q, N_kv, Q.dtype)      # configs 1 and 3 split the key range, config 2 does not
-    assert (wsb is None) == (ci == 2)
+    wsb = _workspace(cfg.H, cfg.N_q, N_kv, Q.dtype)      # config 3 splits the key range, config 1 runs 128-query workgroups, config 2 neither
+    assert (wsb is None) == (ci != 3)
     wk.wk_attention(Q, K, V, O, lse, workspace=wsb)
     torch.cuda.synchronize()
     rows = sample_rows(cfg.N_q, 256, n_random, seed=ci)

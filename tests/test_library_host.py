@@ -187,7 +187,8 @@ def test_argument_validation_of_the_other_calls():
     assert L.wk_calibration_copy(one, one, 0, None) == wk.WK_OK
     # key-range splits are only proposed when the plain grid would leave compute units idle
     assert wk.wk_attention_workspace_bytes(40, 4680, 28080, wk.WK_BF16) == 0
-    assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) > 12 * 2640 * 128 * 4
+    assert wk.wk_attention_workspace_bytes(12, 2640, 211200, wk.WK_BF16) > 12 * 2640 * 128 * 4   # few items, long window
+    assert wk.wk_attention_workspace_bytes(12, 2640, 10560, wk.WK_BF16) == 0     # short window: 128-query workgroups instead
     assert wk.wk_attention_workspace_bytes(4, 880, 2640, wk.WK_F32) > 4 * 880 * 128 * 4       # the tiny fp32 case splits
     assert wk.wk_attention_workspace_bytes(40, 4680 * 8, 28080, wk.WK_F32) == 0              # enough workgroups as it is
     assert wk.wk_attention_workspace_bytes(4, 880, 2640, 7) == 0                              # unknown element type
