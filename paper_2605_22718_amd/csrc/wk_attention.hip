@@ -1070,6 +1070,8 @@ wk_status allow_large_lds() {
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, true, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<8, false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_bf16<4, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes) != hipSuccess)
             return WK_ERR_HIP;
         wk::mark_device(done, dev);
@@ -1380,12 +1382,20 @@ extern "C" wk_status wk_attention_in_place(const void *Q, const void *K_native, 
     a.n_chunks = 0;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
     a.v_table = store->V_ptr; a.ids = ids; a.n_ids = n_ids; a.R_max = store->M > 0 ? R_max : 0; a.store_M = store->M;
-    a.n_qtiles = (N_q + 255) / 256;
+    // 256- or 128-query workgroups, by the cost model of wk_attention for the longest window the ids can give
+    const long long longest = (long long)n_native + (long long)a.R_max * store->max_tok;
+    const LaunchPlan plan = plan_bf16(a.H, N_q, (int)(longest < 64 ? 64 : (longest > 0x7fffffff ? 0x7fffffff : longest)), false);
+    const int q_per_wg = plan.waves * 32;
+    a.n_qtiles = (N_q + q_per_wg - 1) / q_per_wg;
+    if ((long long)a.H * a.n_qtiles + kXcds > 0x7fffffffLL) return WK_ERR_UNSUPPORTED;
     a.per_xcd = (a.H * a.n_qtiles + kXcds - 1) / kXcds;
     const wk_status rc = allow_large_lds();
     if (rc != WK_OK) return rc;
-    hipLaunchKernelGGL((k_attn_bf16<8, false, true>), dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes,
-                       reinterpret_cast<hipStream_t>(hip_stream), a, SubTable{});
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    if (plan.waves == 8)
+        hipLaunchKernelGGL((k_attn_bf16<8, false, true>), dim3(a.per_xcd * kXcds), dim3(512), kSmemBytes, st, a, SubTable{});
+    else
+        hipLaunchKernelGGL((k_attn_bf16<4, false, true>), dim3(a.per_xcd * kXcds), dim3(256), kSmemBytes, st, a, SubTable{});
     WK_LAUNCH_CHECK();
     return WK_OK;
 }
