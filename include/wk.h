@@ -120,6 +120,26 @@ wk_status wk_compress_chunk(const wk_compress_desc *desc, const void *K, const v
                             int32_t *n_out, void *workspace, size_t workspace_bytes,
                             void *hip_stream);
 
+/* For callers that cannot allocate device memory or pass a workspace along (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): wk_compress_chunk with the same
+ * arguments, results and errors, minus the workspace, which is a fixed array of
+ * WK_COMPRESS_SCRATCH_BYTES built into the library (each GPU the library runs on holds one until the
+ * process ends).  The call allocates and frees nothing.  One LingBot-sized chunk (H = 40, T = 1,560,
+ * F = 3) fits in either head mode with factored scoring and in shared-head mode with GEMM scoring.
+ *   - WK_ERR_WORKSPACE if wk_compress_workspace_bytes(desc) exceeds WK_COMPRESS_SCRATCH_BYTES (nothing
+ *     is launched); WK_ERR_HIP if the array's address cannot be resolved.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (different
+ *     streams, or different host threads) race; keep them in order on one stream.  The array keeps the
+ *     last call's contents; no call depends on them.
+ *   - The first call on a device resolves the array's device address (a runtime query, not a stream
+ *     operation); make one call on the device before capturing a graph that holds this call.
+ *   - The Eq. 5 scores are not readable by the caller here (the array is private to the library). */
+#define WK_COMPRESS_SCRATCH_BYTES (4u << 20)
+size_t wk_compress_scratch_bytes(void);
+wk_status wk_compress_chunk_noalloc(const wk_compress_desc *desc, const void *K, const void *V,
+                                    const void *K_anchor, int32_t *kept_idx, void *K_out, void *V_out,
+                                    int32_t *n_out, void *hip_stream);
+
 #define WK_SCORE_MAX_CHUNKS 4096
 
 /* World Retrieval (Sec. 4.2, Eq. 4) with the camera/action distance of Sec. 5.1: for every

@@ -25,7 +25,8 @@ WK_SCORE_MAX_CHUNKS = 4096
 WK_QUERY_MAX_CHUNKS = 1024
 
 EXPORTS = [
-    "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_score_chunks",
+    "wk_keep_count", "wk_compress_workspace_bytes", "wk_compress_chunk", "wk_compress_chunk_noalloc",
+    "wk_compress_scratch_bytes", "wk_score_chunks",
     "wk_score_chunks_query", "wk_score_chunks_query_workspace_bytes", "wk_chunk_lse",
     "wk_attention_block_causal", "wk_attention_block_causal_workspace_bytes",
     "wk_window_plan", "wk_window_update", "wk_window_update_workspace_bytes",
@@ -85,6 +86,10 @@ def lib():
         L.wk_compress_chunk.restype = C.c_int
         L.wk_compress_chunk.argtypes = [C.POINTER(wk_compress_desc), vp, vp, vp, vp, vp, vp, C.POINTER(i32),
                                         vp, C.c_size_t, vp]
+        L.wk_compress_chunk_noalloc.restype = C.c_int
+        L.wk_compress_chunk_noalloc.argtypes = [C.POINTER(wk_compress_desc), vp, vp, vp, vp, vp, vp, C.POINTER(i32), vp]
+        L.wk_compress_scratch_bytes.restype = C.c_size_t
+        L.wk_compress_scratch_bytes.argtypes = []
         L.wk_score_chunks.restype = C.c_int
         L.wk_score_chunks.argtypes = [vp, i32, C.POINTER(f32), i32, i32, vp, vp, vp, vp]
         L.wk_attention_in_place.restype = C.c_int
@@ -211,6 +216,20 @@ def wk_compress_chunk(desc: wk_compress_desc, K, V, K_anchor, kept_idx, K_out, V
                                  C.byref(n_out), _dev(workspace, "workspace"),
                                  0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(st, "wk_compress_chunk")
+    return n_out.value
+
+
+def wk_compress_scratch_bytes() -> int:
+    return lib().wk_compress_scratch_bytes()
+
+
+def wk_compress_chunk_noalloc(desc: wk_compress_desc, K, V, K_anchor, kept_idx, K_out, V_out) -> int:
+    """wk_compress_chunk_noalloc: wk_compress_chunk on the library's built-in scratch array; returns n_out."""
+    n_out = C.c_int32()
+    st = lib().wk_compress_chunk_noalloc(C.byref(desc), _dev(K, "K"), _dev(V, "V"), _dev(K_anchor, "K_anchor"),
+                                         _dev(kept_idx, "kept_idx", torch.int32), _dev(K_out, "K_out"),
+                                         _dev(V_out, "V_out"), C.byref(n_out), _stream())
+    _check(st, "wk_compress_chunk_noalloc")
     return n_out.value
 
 

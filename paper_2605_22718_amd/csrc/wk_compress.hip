@@ -180,14 +180,6 @@ __global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__
     }
 }
 
-// ---- Eq. 5 as a similarity GEMM on the matrix cores (bf16) -------------------------------------
-//
-// scores_j = (1/T) sum_i (k_j . k_i) / (|k_j| |k_i|).  A workgroup owns 64 candidates; for each tile
-// of 64 anchors it accumulates the 64 x 64 block of dot products over all heads of the group
-// (v_mfma_f32_32x32x16_bf16, one 32 x 32 sub-block per wave, raw bf16 keys so every product is exact
-// in fp32), then the epilogue scales column i by 1/|k_i| and adds it into a per-candidate running sum:
-// the (F-1)T x T matrix never leaves registers.  Lane l of a wave holds anchor column l % 32 and
-// candidate rows 8*(r/4) + 4*(l/32) + r%4, so the column scale is a per-lane scalar.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 // ---- Eq. 5 as the similarity GEMM on the matrix cores (WK_SCORE_GEMM) ------------------------
@@ -704,6 +696,64 @@ extern "C" wk_status wk_compress_chunk(const wk_compress_desc *desc, const void 
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return WK_ERR_WORKSPACE;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     char *wsp = reinterpret_cast<char *>(workspace);
+    if (desc->dtype == WK_BF16)
+        st = launch_all<WK_BF16>(desc, p, ws, K, V, K_anchor, kept_idx, K_out, V_out, wsp, stream);
+    else
+        st = launch_all<WK_F32>(desc, p, ws, K, V, K_anchor, kept_idx, K_out, V_out, wsp, stream);
+    if (st == WK_OK && n_out) *n_out = no;
+    return st;
+}
+
+// ---- wk_compress_chunk for callers that cannot allocate ----------------------------------------
+// The workspace of wk_compress_chunk (scores, squared norms, the anchor mean and its partial sums,
+// the index list when the caller wants none) lives in this array instead of a caller's buffer.  Every
+// device the library runs on holds its own copy at its own address; in host code the array's name
+// is only a handle for hipGetSymbolAddress, never an address a kernel may be given.
+static __device__ __align__(256) unsigned char scratch[WK_COMPRESS_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_addr[kMaxDevices];   // device address of `scratch`, per device (null: not asked yet)
+
+// The current device's copy of `scratch`; resolved once per device, with that device current.
+wk_status scratch_of_current_device(char **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return WK_ERR_HIP;
+    void *ptr = dev < kMaxDevices ? scratch_addr[dev].load(std::memory_order_acquire) : nullptr;
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return WK_ERR_HIP;
+        if (dev < kMaxDevices) scratch_addr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = reinterpret_cast<char *>(ptr);
+    return WK_OK;
+}
+
+}  // namespace
+
+extern "C" size_t wk_compress_scratch_bytes(void) { return WK_COMPRESS_SCRATCH_BYTES; }
+
+extern "C" wk_status wk_compress_chunk_noalloc(const wk_compress_desc *desc, const void *K, const void *V,
+                                               const void *K_anchor, int32_t *kept_idx, void *K_out,
+                                               void *V_out, int32_t *n_out, void *hip_stream) {
+    wk_status st = check_desc(desc);
+    if (st != WK_OK) return st;
+    if (!K || !V || !K_out || !V_out) return WK_ERR_INVALID_ARG;
+    const bool ext = desc->anchor_mode == WK_ANCHOR_EXTERNAL;
+    if (ext != (K_anchor != nullptr)) return WK_ERR_INVALID_ARG;
+    int32_t no = 0, nk = 0;
+    st = wk_keep_count(desc->rho, desc->ratio_kind, desc->anchor_mode, desc->F, desc->T, &no, &nk);
+    if (st != WK_OK) return st;
+    CompressDims p;
+    WsLayout ws;
+    if (!make_dims(desc, p, ws)) return WK_ERR_INVALID_ARG;
+    if (ws.total > WK_COMPRESS_SCRATCH_BYTES) return WK_ERR_WORKSPACE;   // larger than the built-in scratch
+    char *wsp = nullptr;
+    st = scratch_of_current_device(&wsp);
+    if (st != WK_OK) return st;
+    // Nothing in the workspace has to start at zero: every kernel of the call writes each element it
+    // or a later kernel reads (scores, norms, mean partials, similarity partials, the index list).
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (desc->dtype == WK_BF16)
         st = launch_all<WK_BF16>(desc, p, ws, K, V, K_anchor, kept_idx, K_out, V_out, wsp, stream);
     else
