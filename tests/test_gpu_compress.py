@@ -36,9 +36,9 @@ def _gpu_compress(cfg, K, V, K_anchor, batch=1, head_mode=wk.WK_HEADS_SHARED, rh
     return idx.cpu().numpy(), Ko.cpu(), Vo.cpu(), scores, n_out
 
 
-def _compare_chunk(cfg, K, V, K_anchor, g_idx, g_K, g_V, g_scores, head_mode, rho, ratio_kind):
-    o_idx, o_K, o_V, o_scores = oracle.compress(K, V, K_anchor, cfg.T, cfg.F, rho, ratio_kind, head_mode,
-                                                cfg.anchor_mode)
+def _compare_chunk(cfg, K, V, K_anchor, g_idx, g_K, g_V, g_scores, head_mode, rho, ratio_kind, oracle_result=None):
+    o_idx, o_K, o_V, o_scores = oracle_result or oracle.compress(K, V, K_anchor, cfg.T, cfg.F, rho, ratio_kind,
+                                                                 head_mode, cfg.anchor_mode)
     assert np.abs(g_scores - o_scores).max() <= SCORE_TOL, np.abs(g_scores - o_scores).max()
     first = 0 if cfg.anchor_mode == wk.WK_ANCHOR_EXTERNAL else cfg.T
     for g in range(o_idx.shape[0]):
@@ -179,3 +179,42 @@ def test_lingbot_sized_batch_sampled(head_mode, algo):
             for h in (0, 17, 39):
                 s_idx = torch.as_tensor(gi[b, h if head_mode == wk.WK_HEADS_INDEPENDENT else 0], dtype=torch.long)
                 assert torch.equal(bits(gK[b, h]), bits(Kc[h, s_idx])) and torch.equal(bits(gV[b, h]), bits(Vc[h, s_idx]))
+
+
+# ---- one full LingBot-sized chunk (configs 2 and 4: H = 40, T = 1,560, F = 3) against the whole oracle ----
+_ORACLE_CACHE = {}
+
+
+def _lingbot_chunk():
+    if "chunk" not in _ORACLE_CACHE:
+        cfg = ws.get_config(2)
+        K, V, _ = ws.make_chunk(cfg, 3, dev())       # generated once on the GPU; both sides get these bytes
+        _ORACLE_CACHE["chunk"] = (cfg, K.cpu(), V.cpu())
+    return _ORACLE_CACHE["chunk"]
+
+
+def _lingbot_oracle(head_mode, rho, kind):
+    """oracle.compress of the whole chunk (Eq. 5 double loop over 3,120 x 1,560 x 40 heads), cached per setting."""
+    key = (head_mode, rho, kind)
+    if key not in _ORACLE_CACHE:
+        cfg, K, V = _lingbot_chunk()
+        _ORACLE_CACHE[key] = oracle.compress(K, V, None, cfg.T, cfg.F, rho, kind, head_mode)
+    return _ORACLE_CACHE[key]
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("algo", [wk.WK_SCORE_FACTORED, wk.WK_SCORE_GEMM])
+@pytest.mark.parametrize("head_mode,rho,kind,n_out", [
+    (wk.WK_HEADS_SHARED, 0.5, wk.WK_RATIO_CHUNK, 2340),          # config 2's setting (3 frames -> 1.5)
+    (wk.WK_HEADS_SHARED, 0.25, wk.WK_RATIO_NONANCHOR, 2340),     # the same count stated as P = 25 %
+    (wk.WK_HEADS_SHARED, 0.75, wk.WK_RATIO_NONANCHOR, 3900),     # config 4's upper ratio
+    (wk.WK_HEADS_INDEPENDENT, 0.25, wk.WK_RATIO_NONANCHOR, 2340),
+])
+def test_lingbot_sized_chunk_full_oracle_compare(head_mode, rho, kind, n_out, algo):
+    """Every one of the 3,120 candidate scores (x 40 lists with per-head index sets), the kept-index sets and
+    the compacted rows of a LingBot-sized chunk against oracle.compress."""
+    cfg, K, V = _lingbot_chunk()
+    gi, gK, gV, gs, got = _gpu_compress(cfg, K, V, None, head_mode=head_mode, rho=rho, ratio_kind=kind, score_algo=algo)
+    assert got == n_out
+    same = _compare_chunk(cfg, K, V, None, gi[0], gK[0], gV[0], gs[0], head_mode, rho, kind, oracle_result=_lingbot_oracle(head_mode, rho, kind))
+    print(f"LingBot chunk, head_mode {head_mode}, rho {rho}, algo {algo}: index sets identical to the oracle: {same}")

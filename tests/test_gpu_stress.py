@@ -1,8 +1,9 @@
 """Config 4 (compression / retrieval stress at the LingBot shape) at full size on the GPU:
 a batch of 64 chunks compressed at P in {0.25, 0.5, 0.75}, top-16 retrieval over a 1,000-chunk store
 indexed by walked poses and by integrated action labels, and the window gathered from pinned host
-memory.  At this size the oracle checks sampled outputs; the rest is checked by properties that hold
-at any size (exact selection of the GPU's own scores, byte-exact copies)."""
+memory.  One chunk of the batch is compressed by the whole oracle at each ratio (all scores, kept-index set,
+compacted rows); for the other 63 the oracle checks sampled scores and the rest is checked by properties
+that hold at any size (exact selection of the GPU's own scores, byte-exact copies)."""
 import numpy as np
 import pytest
 import torch
@@ -10,7 +11,7 @@ import torch
 import oracle
 import paper_2605_22718_amd as wk
 import wk_synth as ws
-from wkt import bits, dev
+from wkt import assert_selection_matches, bits, dev
 
 pytestmark = pytest.mark.gpu
 BATCH, POOL = 64, 64
@@ -28,11 +29,25 @@ def batch64():
     return cfg, K, V
 
 
+_ORACLE_CHUNK = 5      # the chunk of the batch that the whole oracle compresses, once per ratio
+_ORACLE_CACHE = {}
+
+
+def _oracle_chunk(cfg, K, V, P):
+    if P not in _ORACLE_CACHE:
+        _ORACLE_CACHE[P] = oracle.compress(K[_ORACLE_CHUNK].cpu(), V[_ORACLE_CHUNK].cpu(), None, cfg.T, cfg.F, P,
+                                           wk.WK_RATIO_NONANCHOR)
+    return _ORACLE_CACHE[P]
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("algo", [wk.WK_SCORE_FACTORED, wk.WK_SCORE_GEMM])
 @pytest.mark.parametrize("P,n_out", [(0.25, 2340), (0.5, 3120), (0.75, 3900)])
-def test_batch_compress_at_three_ratios(batch64, P, n_out):
+def test_batch_compress_at_three_ratios(batch64, P, n_out, algo):
     cfg, K, V = batch64
     d = dev()
-    desc = wk.make_compress_desc(cfg.H, cfg.T, cfg.F, cfg.dtype, P, batch=BATCH, ratio_kind=wk.WK_RATIO_NONANCHOR)
+    desc = wk.make_compress_desc(cfg.H, cfg.T, cfg.F, cfg.dtype, P, batch=BATCH, ratio_kind=wk.WK_RATIO_NONANCHOR,
+                                 score_algo=algo)
     wsb = torch.empty(wk.wk_compress_workspace_bytes(desc), dtype=torch.uint8, device=d)
     idx = torch.empty((BATCH, 1, n_out), dtype=torch.int32, device=d)
     Ko = torch.empty((BATCH, cfg.H, n_out, cfg.d), dtype=torch.bfloat16, device=d)
@@ -52,10 +67,19 @@ def test_batch_compress_at_three_ratios(batch64, P, n_out):
     for b in (0, 31, 63):
         sel = gi[b]
         assert torch.equal(bits(Ko[b]), bits(K[b][:, sel])) and torch.equal(bits(Vo[b]), bits(V[b][:, sel]))
-    # oracle scores on sampled candidates of two chunks
+    # one chunk of the batch against the whole oracle: all 3,120 scores, the kept-index set, the compacted rows
+    o_idx, o_K, o_V, o_scores = _oracle_chunk(cfg, K, V, P)
+    b = _ORACLE_CHUNK
+    assert np.abs(scores[b].cpu().numpy() - o_scores[0]).max() <= 1e-7
+    g_idx = idx[b, 0].cpu().numpy()
+    np.testing.assert_array_equal(g_idx[:cfg.T], o_idx[0, :cfg.T])
+    assert_selection_matches(g_idx[cfg.T:] - cfg.T, o_idx[0, cfg.T:] - cfg.T, o_scores[0], f"chunk {b} at P={P}")
+    if np.array_equal(g_idx, o_idx[0]):
+        assert torch.equal(bits(Ko[b].cpu()), bits(o_K)) and torch.equal(bits(Vo[b].cpu()), bits(o_V))
+    # oracle scores on sampled candidates of two more chunks
     rng = np.random.default_rng(int(P * 100))
     sel = np.unique(np.concatenate([[0, n_cand - 1], rng.integers(0, n_cand, 24)])).astype(np.int32)
-    for b in (5, 40):
+    for b in (17, 40):
         o = oracle.compress_scores(K[b].cpu(), None, cfg.T, cfg.F, cand_sel=sel)
         assert np.abs(scores[b].cpu().numpy()[sel] - o[0, sel]).max() <= 1e-7
 
