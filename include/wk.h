@@ -195,7 +195,9 @@ typedef struct wk_store_desc {
     const void *const *V_ptr; /* device array [M]: same for values */
     const int32_t *n_tok;     /* device array [M]: stored tokens of chunk c */
     int32_t M;                /* chunks in the store */
-    int32_t max_tok;          /* host-known upper bound of n_tok[] */
+    int32_t max_tok;          /* host-known upper bound of n_tok[]: a hard bound.  Buffers and offsets are sized
+                                 by it on the host; a chunk whose n_tok[c] exceeds it is treated as absent
+                                 (skipped, like an id outside [0, M)) by every call that reads the store */
     int32_t H, d, dtype;
 } wk_store_desc;
 
@@ -205,7 +207,7 @@ typedef struct wk_store_desc {
  * store, Sec. 7); ids and n_ids come from wk_score_chunks and are read on the device, so no
  * host synchronisation separates the two calls.
  *
- *   ids        device, [R_max] int32; entries < 0 or >= M are skipped
+ *   ids        device, [R_max] int32; entries < 0 or >= M, and chunks with n_tok > max_tok, are skipped
  *   n_ids      device, int32; only the first min(*n_ids, R_max) ids are used.  NULL = R_max.
  *   K_native,V_native device, [H][n_native][d]; NULL with n_native > 0 means the native rows
  *              are already in place in the window and are not copied
@@ -237,7 +239,8 @@ wk_status wk_gather_window(const wk_store_desc *store, const int32_t *ids, const
  *              over several workgroups whose partial results are merged by a second kernel; that
  *              needs wk_attention_workspace_bytes(...) bytes.  Without (enough) workspace the call
  *              runs unsplit: same result up to fp32 rounding order, lower occupancy.
- * Errors: INVALID_ARG, UNSUPPORTED (d != 128), SHAPE (N_kv < 1 or N_kv > kv_row_stride). */
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128; bf16 with N_kv > 2^24 - 512 rows), SHAPE (N_kv < 1 or
+ *         N_kv > kv_row_stride). */
 wk_status wk_attention(const void *Q, const void *K_win, const void *V_win, void *O, float *lse,
                        int32_t H, int32_t N_q, int32_t N_kv, int32_t d, int32_t kv_row_stride,
                        int32_t dtype, float scale, const int32_t *n_kv_dev, void *workspace,
@@ -257,8 +260,8 @@ size_t wk_attention_workspace_bytes(int32_t H, int32_t N_q, int32_t N_kv, int32_
  *   n_kv_dev   if given, *n_kv_dev must be >= denoise_row0 + N_q (the chunk lies inside the window)
  *   workspace  device, 256-byte aligned, wk_attention_block_causal_workspace_bytes(H, N_q) bytes:
  *              the two visible key ranges of a query are attended separately and merged
- * Errors: INVALID_ARG, UNSUPPORTED (d != 128), SHAPE (N_kv, or N_q not a multiple of frame_T, or
- * the chunk's rows run past N_kv), WORKSPACE. */
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128; bf16 with N_kv > 2^24 - 512 rows), SHAPE (N_kv, or N_q not a
+ * multiple of frame_T, or the chunk's rows run past N_kv), WORKSPACE. */
 wk_status wk_attention_block_causal(const void *Q, const void *K_win, const void *V_win, void *O,
                                     float *lse, int32_t H, int32_t N_q, int32_t N_kv, int32_t d,
                                     int32_t kv_row_stride, int32_t dtype, float scale,
@@ -299,7 +302,7 @@ wk_status wk_attention_in_place(const void *Q, const void *K_native, const void 
  *   Q          device, [H][N_q][d], element type store->dtype
  *   scale      logit scale; 0 means 1/sqrt(d)
  *   lse_out    device out, [M][H][N_q] float; -inf where a chunk holds no token
- * Errors: INVALID_ARG, UNSUPPORTED (d != 128, or more than 2^31 workgroups). */
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, more than 2^31 workgroups, bf16 with max_tok > 2^24 - 512). */
 wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int32_t N_q, float scale,
                        float *lse_out, void *hip_stream);
 
@@ -355,7 +358,8 @@ wk_status wk_window_plan(const wk_window_desc *w, int64_t chunk_index, wk_window
  *   n_fetched  device out, int32 = chunks copied by this call.  May be NULL.
  *   workspace  device, wk_window_update_workspace_bytes(R) bytes, 256-byte aligned
  *   max_workgroups  > 0 caps the copy grid (see wk_prefetch_gather); 0 = one per 32 KB
- * Errors: INVALID_ARG, UNSUPPORTED (d != 128, R > 1024), SHAPE (slots exceed win_capacity), WORKSPACE. */
+ * Errors: INVALID_ARG, UNSUPPORTED (d != 128, R > 1024), SHAPE (slots exceed win_capacity, or slot_tokens
+ *         exceeds the store's max_tok), WORKSPACE. */
 wk_status wk_window_update(const wk_store_desc *store, const int32_t *ids, const int32_t *n_ids, int32_t R,
                            int32_t slot_tokens, int32_t *slot_ids, int32_t n_native, void *K_win,
                            void *V_win, int32_t win_capacity, int32_t *n_win, int32_t *n_fetched,

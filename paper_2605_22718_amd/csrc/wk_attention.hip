@@ -57,7 +57,13 @@ struct AttnArgs {
     const int32_t *ids;
     const int32_t *n_ids;
     int R_max, store_M;
+    // host-known upper bound of n_tok[] (store descriptors): a chunk that claims more rows is treated as
+    // absent, so no length the host has not seen can reach the 32-bit byte offsets of the tile loads
+    int max_tok;
 };
+
+// bf16 tile loads form 32-bit byte offsets of rows (256 B each), up to four tiles past the last one
+constexpr int kMaxRowsBf16 = (1 << 24) - 512;
 
 constexpr int kXcds = 8;
 
@@ -115,6 +121,7 @@ __device__ inline Window window_of(const AttnArgs &a, int c) {
     if (a.n_chunks > 0) {
         w.K = reinterpret_cast<const char *>(a.k_table[c]);
         w.n_kv = w.stride = a.n_tok[c];
+        if (w.n_kv > a.max_tok) w.n_kv = 0;   // violates the descriptor's bound: holds no token
         w.lse = a.lse + (size_t)c * a.H * a.q_rows;
     } else {
         w.K = a.K;
@@ -384,7 +391,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
                 const int id = tid - 1 < nf ? a.ids[tid - 1] : -1;
                 if (id >= 0 && id < a.store_M) {
                     const int len = a.n_tok[id];
-                    if (len > 0)
+                    if (len > 0 && len <= a.max_tok)   // a chunk beyond the descriptor's bound is skipped
                         e = Segment{reinterpret_cast<const char *>(a.k_table[id]) + (size_t)h * len * 256,
                                     reinterpret_cast<const char *>(a.v_table[id]) + (size_t)h * len * 256, len, 0};
                 }
@@ -1121,6 +1128,7 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     if (!(scale >= 0.f) || std::isinf(scale)) return WK_ERR_INVALID_ARG;
     if (d != WK_D) return WK_ERR_UNSUPPORTED;
     if (N_kv < 1 || N_kv > kv_row_stride) return WK_ERR_SHAPE;
+    if (dtype == WK_BF16 && N_kv > kMaxRowsBf16) return WK_ERR_UNSUPPORTED;   // 32-bit byte offsets inside a head
     if (N_q == 0) return WK_OK;
     if ((long long)H * ((N_q + 31) / 32) > 0x7fffffffLL / kMaxSplits) return WK_ERR_UNSUPPORTED;   // grid size
     AttnArgs a;
@@ -1140,7 +1148,7 @@ extern "C" wk_status wk_attention(const void *Q, const void *K_win, const void *
     a.n_tok = nullptr;
     a.n_chunks = 0;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
-    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0;
+    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0; a.max_tok = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     if (dtype == WK_F32) {
         const int q_per_wg = kF32Waves * 32;
@@ -1222,6 +1230,7 @@ extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win,
     if (d != WK_D) return WK_ERR_UNSUPPORTED;
     if (N_kv < 1 || N_kv > kv_row_stride) return WK_ERR_SHAPE;
     if (N_q % frame_T != 0 || (int64_t)denoise_row0 + N_q > (int64_t)N_kv) return WK_ERR_SHAPE;
+    if (dtype == WK_BF16 && N_kv > kMaxRowsBf16) return WK_ERR_UNSUPPORTED;   // 32-bit byte offsets inside a head
     if (N_q == 0) return WK_OK;
     if (!workspace || workspace_bytes < split_workspace_bytes(H, N_q, 2) ||
         reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
@@ -1243,7 +1252,7 @@ extern "C" wk_status wk_attention_block_causal(const void *Q, const void *K_win,
                                           wk::align_up((size_t)2 * H * N_q * WK_D * sizeof(float), 256));
     a.k_table = nullptr; a.n_tok = nullptr; a.n_chunks = 0;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
-    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0;
+    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0; a.max_tok = 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
 
     const int frames = N_q / frame_T;
@@ -1312,6 +1321,7 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
     if (store->dtype != WK_F32 && store->dtype != WK_BF16) return WK_ERR_INVALID_ARG;
     if (!(scale >= 0.f) || std::isinf(scale)) return WK_ERR_INVALID_ARG;
     if (store->d != WK_D) return WK_ERR_UNSUPPORTED;
+    if (store->dtype == WK_BF16 && store->max_tok > kMaxRowsBf16) return WK_ERR_UNSUPPORTED;   // 32-bit byte offsets
     if (store->M == 0 || N_q == 0) return WK_OK;
     if (!store->K_ptr || !store->n_tok) return WK_ERR_INVALID_ARG;
     AttnArgs a;
@@ -1330,7 +1340,7 @@ extern "C" wk_status wk_chunk_lse(const wk_store_desc *store, const void *Q, int
     a.n_tok = store->n_tok;
     a.n_chunks = store->M;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
-    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0;
+    a.v_table = nullptr; a.ids = nullptr; a.n_ids = nullptr; a.R_max = 0; a.store_M = 0; a.max_tok = store->max_tok;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int q_per_wg = (store->dtype == WK_F32 ? kF32Waves : 8) * 32;
     const long long items = (long long)store->M * store->H * ((N_q + q_per_wg - 1) / q_per_wg);
@@ -1382,6 +1392,7 @@ extern "C" wk_status wk_attention_in_place(const void *Q, const void *K_native, 
     a.n_chunks = 0;
     a.q_rows = N_q; a.q_off = 0; a.kv_start = 0; a.part_slot = -1;
     a.v_table = store->V_ptr; a.ids = ids; a.n_ids = n_ids; a.R_max = store->M > 0 ? R_max : 0; a.store_M = store->M;
+    a.max_tok = store->max_tok;
     // 256- or 128-query workgroups, by the cost model of wk_attention for the longest window the ids can give
     const long long longest = (long long)n_native + (long long)a.R_max * store->max_tok;
     const LaunchPlan plan = plan_bf16(a.H, N_q, (int)(longest < 64 ? 64 : (longest > 0x7fffffff ? 0x7fffffff : longest)), false);

@@ -63,7 +63,10 @@ __global__ __launch_bounds__(kThreads) void k_gather(GatherArgs a) {
         const char *k = nullptr, *v = nullptr;
         if (id >= 0 && id < a.M) {
             len = a.n_tok[id];
-            len = len < 0 ? 0 : (len > a.max_tok ? a.max_tok : len);
+            // a chunk that claims more rows than the descriptor's bound is skipped, like an id outside the
+            // store: its length is the stride between its heads, so it cannot be cut short, and the window
+            // was sized by the host for max_tok rows per chunk
+            if (len < 0 || len > a.max_tok) len = 0;
             k = reinterpret_cast<const char *>(a.K_ptr[id]);
             v = reinterpret_cast<const char *>(a.V_ptr[id]);
         }

@@ -233,6 +233,7 @@ extern "C" wk_status wk_window_update(const wk_store_desc *store, const int32_t 
     if (R > 0 && store->M > 0 && (!store->K_ptr || !store->V_ptr || !store->n_tok)) return WK_ERR_INVALID_ARG;
     if (store->d != WK_D || R > kMaxSlots) return WK_ERR_UNSUPPORTED;
     if ((int64_t)n_native + (int64_t)R * slot_tokens > (int64_t)win_capacity) return WK_ERR_SHAPE;
+    if (slot_tokens > store->max_tok && store->M > 0) return WK_ERR_SHAPE;   // no chunk within the store's bound fits the slots
     const size_t need = wk_window_update_workspace_bytes(R);
     if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
         return WK_ERR_WORKSPACE;

@@ -117,3 +117,43 @@ def test_calibration_copy_is_exact():
         wk.wk_calibration_copy(dst[:n], src)
         torch.cuda.synchronize()
         assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0
+
+
+def test_chunks_beyond_the_descriptors_bound_are_skipped():
+    """max_tok is a hard bound: a chunk whose n_tok exceeds it is skipped (its head stride is its true length,
+    so it cannot be read cut short), by the gather and by attention in place alike."""
+    import ctypes as C
+    cfg = ws.get_config(1).with_(H=3)
+    lengths = [40, 300, 77, 129]
+    ks, vs, store = _store(cfg, lengths)
+    tight = wk.wk_store_desc(store.K_ptr.data_ptr(), store.V_ptr.data_ptr(), store.n_tok.data_ptr(), len(lengths),
+                             129, cfg.H, cfg.d, store.dtype)          # chunk 1 (300 rows) violates the bound
+    Kn, Vn = ws.make_native(cfg, n_rows=70)
+    ids = [3, 1, 0, 2]
+    cap = 70 + 4 * 129
+    d = dev()
+    Kw = torch.full((cfg.H, cap, cfg.d), 7.0, dtype=torch.bfloat16, device=d)
+    Vw = torch.full_like(Kw, 9.0)
+    n_win = torch.full((1,), -1, dtype=torch.int32, device=d)
+    ids_d = torch.tensor(ids, dtype=torch.int32, device=d)
+    wk.wk_gather_window(tight, ids_d, None, 4, Kn.to(d), Vn.to(d), 70, Kw, Vw, cap, n_win)
+    torch.cuda.synchronize()
+    oK, oV, o_n = oracle.gather(ks, vs, [3, 0, 2], Kn, Vn, cap)
+    assert int(n_win.item()) == o_n == 70 + 129 + 40 + 77
+    assert torch.equal(bits(Kw.cpu()[:, :o_n]), bits(oK[:, :o_n])) and torch.equal(bits(Vw.cpu()[:, :o_n]), bits(oV[:, :o_n]))
+    assert (Kw[:, o_n:] == 7).all()
+    # attention in place skips the same chunk
+    Q = ws.make_queries(cfg, n_q=90)
+    O = torch.empty((cfg.H, 90, cfg.d), dtype=torch.bfloat16, device=d)
+    lse = torch.empty((cfg.H, 90), dtype=torch.float32, device=d)
+    wk.wk_attention_in_place(Q.to(d), Kn.to(d), Vn.to(d), 70, tight, ids_d, None, 4, O, lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.attention(Q, oK, oV, N_kv=o_n, want_lse=True)
+    err = np.abs(O.float().cpu().numpy().astype(np.float64) - ref)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() <= 2e-2
+    # the chunk index for query-based retrieval reports such a chunk as empty
+    out = torch.empty((len(lengths), cfg.H, 90), dtype=torch.float32, device=d)
+    wk.wk_chunk_lse(tight, Q.to(d), out)
+    torch.cuda.synchronize()
+    assert torch.isinf(out[1]).all() and (out[1] < 0).all() and torch.isfinite(out[[0, 2, 3]]).all()

@@ -110,6 +110,10 @@ def test_argument_validation_of_the_other_calls():
     assert attn(dtype=5) == wk.WK_ERR_INVALID_ARG
     assert attn(H=0) == wk.WK_ERR_INVALID_ARG
     assert L.wk_attention(None, one, one, one, None, 2, 8, 8, 128, 8, 1, 0.0, None, None, 0, None) == wk.WK_ERR_INVALID_ARG
+    # bf16 windows beyond what the kernels' 32-bit byte offsets reach are refused, not wrapped around
+    big = (1 << 24) - 511
+    assert attn(N_kv=big, stride=big) == wk.WK_ERR_UNSUPPORTED
+    assert attn(N_kv=1 << 26, stride=1 << 26) == wk.WK_ERR_UNSUPPORTED
     # O == NULL asks for the log-sum-exp only and then needs lse
     assert L.wk_attention(one, one, None, None, None, 2, 8, 8, 128, 8, 1, 0.0, None, None, 0, None) == wk.WK_ERR_INVALID_ARG
     # query-based retrieval
@@ -137,6 +141,8 @@ def test_argument_validation_of_the_other_calls():
     assert L.wk_chunk_lse(C.byref(sd), one, 8, -1.0, one, None) == wk.WK_ERR_INVALID_ARG
     sd64 = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 64, wk.WK_BF16)
     assert L.wk_chunk_lse(C.byref(sd64), one, 8, 0.0, one, None) == wk.WK_ERR_UNSUPPORTED
+    sd_big = wk.wk_store_desc(256, 256, 256, 4, (1 << 24) - 511, 2, 128, wk.WK_BF16)
+    assert L.wk_chunk_lse(C.byref(sd_big), one, 8, 0.0, one, None) == wk.WK_ERR_UNSUPPORTED   # 32-bit byte offsets
     sd0 = wk.wk_store_desc(None, None, None, 0, 0, 2, 128, wk.WK_BF16)
     assert L.wk_chunk_lse(C.byref(sd0), one, 8, 0.0, one, None) == wk.WK_OK      # empty store: nothing to do
     # attention in place over the store
@@ -177,6 +183,8 @@ def test_argument_validation_of_the_other_calls():
     assert bc(T=4) == wk.WK_ERR_SHAPE             # N_q is not a multiple of the frame
     assert bc(row0=15) == wk.WK_ERR_SHAPE         # the chunk's rows run past the window
     assert bc(N_kv=40) == wk.WK_ERR_SHAPE         # beyond the row stride
+    assert L.wk_attention_block_causal(one, one, one, one, None, 2, 6, 1 << 24, 128, 1 << 24, 1, 0.0, None, 4, 3, one,
+                                       1 << 20, None) == wk.WK_ERR_UNSUPPORTED               # 32-bit byte offsets
     assert bc(ws=None) == wk.WK_ERR_WORKSPACE
     assert bc(ws_bytes=100) == wk.WK_ERR_WORKSPACE
     assert wk.wk_attention_block_causal_workspace_bytes(2, 6) >= 2 * 2 * 6 * (128 + 2) * 4
@@ -202,6 +210,10 @@ def test_argument_validation_of_the_other_calls():
         == wk.WK_ERR_UNSUPPORTED
     sd64 = wk.wk_store_desc(256, 256, 256, 4, 10, 2, 64, wk.WK_BF16)
     assert L.wk_gather_window(C.byref(sd64), one, None, 2, one, one, 5, one, one, 25, None, None) == wk.WK_ERR_UNSUPPORTED
+    # window update: slots longer than any chunk the store's bound allows
+    need = wk.wk_window_update_workspace_bytes(2)
+    assert L.wk_window_update(C.byref(sd), one, None, 2, 11, one, 5, one, one, 64, None, None, one, need, 0, None) \
+        == wk.WK_ERR_SHAPE
     assert L.wk_host_device_pointer(None, None) == wk.WK_ERR_INVALID_ARG
 
 
