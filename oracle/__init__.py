@@ -25,7 +25,8 @@ NORM_MAX, NORM_MINMAX, NORM_MEAN = 0, 1, 2
 def lib():
     global _LIB
     if _LIB is None:
-        path = _build.build(force=False)
+        # WK_ORACLE_LIB: an already built library to load instead (the sanitizer run of the oracle's pins)
+        path = os.environ.get("WK_ORACLE_LIB") or _build.build(force=False)
         L = C.CDLL(path)
         L.wko_geodesic.restype = C.c_double
         L.wko_geodesic.argtypes = [C.c_double] * 4

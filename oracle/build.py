@@ -17,6 +17,20 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host checks of the checker itself).
+    The result must be loaded into a process that has gcc's libasan preloaded."""
+    cmd = ["gcc", "-std=c99", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", out_path, SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return out_path
+
+
+def sanitizer_runtime() -> str:
+    """Path of the libasan.so that a process loading a build_sanitized() library must preload."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
+
+
 if __name__ == "__main__":
     print(build(force=True))
     sys.exit(0)

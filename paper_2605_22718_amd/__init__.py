@@ -75,9 +75,11 @@ def lib():
     """The loaded C-ABI library.  Raises if it has not been built."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
-        L = C.CDLL(_LIB_PATH)
+        # WK_LIB: another build of the same library to load instead (the host-sanitizer run of the host tests)
+        path = os.environ.get("WK_LIB") or _LIB_PATH
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(path)
         vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
         L.wk_keep_count.restype = C.c_int
         L.wk_keep_count.argtypes = [f32, i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]

@@ -53,5 +53,41 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+SAN_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+            "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+
+
+def build_host_sanitized(out_dir: str) -> str:
+    """libwk with AddressSanitizer and UndefinedBehaviorSanitizer in its HOST code (argument checks, planners,
+    the host-only entry points); device code is compiled as usual.  The result must be loaded into a process
+    that has the runtime of sanitizer_runtime() preloaded.  Returns the library's path."""
+    os.makedirs(out_dir, exist_ok=True)
+
+    def one(src):
+        obj = os.path.join(out_dir, os.path.basename(src)[:-4] + ".o")
+        flags = [f for f in FLAGS if f != "-O3"] + ["-O1"]
+        r = subprocess.run([HIPCC, *flags, *EXTRA.get(os.path.basename(src), []), *SAN_HOST, "-c", src, "-o", obj],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
+        return obj
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(one, sources()))
+    lib = os.path.join(out_dir, "libwk_hostsan.so")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-fno-gpu-sanitize", "-shared-libsan", "-o", lib, *objs], check=True)
+    return lib
+
+
+def sanitizer_runtime() -> str:
+    """Path of the AddressSanitizer runtime (clang's) that a process loading build_host_sanitized()'s library
+    must preload."""
+    clang = os.path.join(os.path.dirname(os.path.realpath(HIPCC)), "..", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/llvm/bin/clang"
+    return subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], check=True, capture_output=True,
+                          text=True).stdout.strip()
+
+
 if __name__ == "__main__":
     print(build(force=True))
