@@ -415,7 +415,8 @@ wk_status wk_prefetch_acquire(wk_prefetch *p, int32_t slot, void *hip_stream);
  * into the slot waits for them. */
 wk_status wk_prefetch_release(wk_prefetch *p, int32_t slot, void *hip_stream);
 
-/* Measurement aid, not a step of the method: a straight device copy of `bytes` bytes (a multiple of
+/* ---- Measurement aid -------------------------------------------------------------------------
+ * Not a step of the method and not needed by any caller of the path: a straight device copy of `bytes` bytes (a multiple of
  * 16, both pointers 16-byte aligned, ranges must not overlap) with ordinary cached 16-byte loads and
  * stores.  Profilers' HBM byte counters are calibrated against it: it moves a known number of bytes
  * with the access pattern of the attention kernels' tile loads.  Errors: INVALID_ARG. */

@@ -40,6 +40,13 @@ def n_threads() -> int:
     return int(v) if v else (os.cpu_count() or 1)
 
 
+def set_threads(n: int) -> None:
+    """Number of OpenMP threads for the following oracle calls (the library links libgomp)."""
+    lib()
+    C.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+    os.environ["OMP_NUM_THREADS"] = str(int(n))
+
+
 def _code(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return F32
