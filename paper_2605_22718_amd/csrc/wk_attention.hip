@@ -342,6 +342,19 @@ __device__ inline float max_across_halves(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// registers the hand-scheduled loop uses beyond its operands: the odd-position S^T tile, P, the K and V^T
+// fragment buffers and three temporaries
+#define WK_ATTN_LOOP_CLOBBERS \
+    "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107", \
+    "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", \
+    "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "v160", "v161", "v162", "v163", \
+    "v164", "v165", "v166", "v167", "v168", "v169", "v170", "v171", "v172", "v173", "v174", "v175", \
+    "v176", "v177", "v178", "v179", "v180", "v181", "v182", "v183", "v184", "v185", "v186", "v187", \
+    "v188", "v189", "v190", "v191", "v192", "v193", "v194", "v195", "v196", "v197", "v198", "v199", \
+    "v200", "v201", "v202", "v203", "v204", "v205", "v206", "v207", "v208", "v209", "v210", "v211", \
+    "v212", "v213", "v214", "v215", "v216", "v217", "v218", "v219", "v220", "v221", "v222", "v223", \
+    "v244", "v245", "v246"
+
 #define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
@@ -744,6 +757,43 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         if (sh == 1) { step(j++, P1{}, s_b, s_a); step(j++, P2{}, s_a, s_b); step(j++, P3{}, s_b, s_a); }
         else if (sh == 2) { step(j++, P2{}, s_a, s_b); step(j++, P3{}, s_b, s_a); }
         else if (sh == 3) { step(j++, P3{}, s_b, s_a); }
+    }
+    if constexpr (WAVES == 8 && !MULTI && !IN_PLACE) {
+        // Steady state: whole groups of four steps whose look-ahead loads all lie inside the window run in the
+        // hand-scheduled loop of wk_attn_loop_gfx950.inc (written by gen_attn_loop.py, which documents its schedule
+        // and register map).  It is the four `step`s below instruction for instruction in what it computes -- same
+        // ring protocol, same arithmetic in the same order, bit-identical results -- so the steps before and behind
+        // it stay in C++: the partial first group, the last steps, whose loads are clamped to the window, and the
+        // last, possibly partial tile.  Its operands are pinned to the registers its text names.
+        int G = (n_kv / kKeys - 4 - t0 - j) / 4;
+        const int G_steps = (n_steps - j) / 4;
+        G = G < G_steps ? G : G_steps;
+        if (G > 0) {
+            unsigned ad[12];
+#pragma unroll
+            for (int st = 0; st < 8; ++st) ad[st] = (unsigned)(size_t)WK_LDS(k_rd[st]);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) ad[8 + b] = (unsigned)(size_t)WK_LDS(v_rd[b]);
+            const unsigned koff = (unsigned)(t0 + j + 4) * (kKeys * 256u), voff = (unsigned)(t0 + j + 3) * (kKeys * 256u);
+            const unsigned dst = (unsigned)(size_t)WK_LDS(dma_dst);
+            int g_left = G;
+            const bf16x8 q0 = qb[0], q1 = qb[1], q2 = qb[2], q3 = qb[3], q4 = qb[4], q5 = qb[5], q6 = qb[6], q7 = qb[7];
+            f32x16 o0 = o[0], o1 = o[1], o2 = o[2], o3 = o[3], sa0 = s_a[0], sa1 = s_a[1];
+            const unsigned ks0 = k_src[0], ks1 = k_src[NB - 1], vs0 = v_src[0], vs1 = v_src[NB - 1];
+            asm volatile(
+#include "wk_attn_loop_gfx950.inc"
+                : "+{v[0:15]}"(o0), "+{v[16:31]}"(o1), "+{v[32:47]}"(o2), "+{v[48:63]}"(o3), "+{v[64:79]}"(sa0),
+                  "+{v[80:95]}"(sa1), "+{v240}"(m_run), "+{v241}"(l_run), "+{v243}"(mt), "+{s44}"(g_left)
+                : "{v[128:131]}"(q0), "{v[132:135]}"(q1), "{v[136:139]}"(q2), "{v[140:143]}"(q3), "{v[144:147]}"(q4),
+                  "{v[148:151]}"(q5), "{v[152:155]}"(q6), "{v[156:159]}"(q7), "{v224}"(ad[0]), "{v225}"(ad[1]),
+                  "{v226}"(ad[2]), "{v227}"(ad[3]), "{v228}"(ad[4]), "{v229}"(ad[5]), "{v230}"(ad[6]), "{v231}"(ad[7]),
+                  "{v232}"(ad[8]), "{v233}"(ad[9]), "{v234}"(ad[10]), "{v235}"(ad[11]), "{v236}"(ks0), "{v237}"(ks1),
+                  "{v238}"(vs0), "{v239}"(vs1), "{s[36:37]}"(Kh), "{s[38:39]}"(Vh), "{s40}"(koff), "{s41}"(voff),
+                  "{s42}"(dst), "{s43}"(c_log2)
+                : WK_ATTN_LOOP_CLOBBERS, "s45", "vcc", "memory");
+            o[0] = o0; o[1] = o1; o[2] = o2; o[3] = o3; s_a[0] = sa0; s_a[1] = sa1;
+            j += 4 * G;
+        }
     }
     for (; j < n_steps; j += 4) {
         step(j, P0{}, s_a, s_b);

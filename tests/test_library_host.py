@@ -340,3 +340,17 @@ def test_header_is_c99_and_a_c_program_sees_what_the_binding_sees(tmp_path):
         assert lines[4 + c] == "plan %d %d %d %d %d %d %d %d %d %d %d" % (
             c, s.denoise_row0, s.denoise_rows, s.n_native, s.evict, s.evict_row0, s.store_id, s.evict_chunk, s.M,
             s.retrieved_row0, s.win_capacity)
+
+
+def test_the_hand_scheduled_attention_loop_is_what_its_generator_writes():
+    """csrc/wk_attn_loop_gfx950.inc is committed as written by csrc/gen_attn_loop.py: regenerate and compare."""
+    import importlib.util
+    csrc = os.path.join(ROOT, "paper_2605_22718_amd", "csrc")
+    spec = importlib.util.spec_from_file_location("gen_attn_loop", os.path.join(csrc, "gen_attn_loop.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    assert gen.render() == open(os.path.join(csrc, "wk_attn_loop_gfx950.inc")).read()
+    lines = gen.generate()
+    # four steps of 32 matrix instructions; the products kept back by the last step stand behind the loop once more
+    assert sum(l.startswith("v_mfma") for l in lines) == 4 * 32 + gen.DEFER
+    assert sum(l == "s_barrier" for l in lines) == 4
