@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM bytes per wk_attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
 # scaled by what the counter reads for the plain calibration copy (0.500 and 1.000), per workload index;
 # see profiles/hbm_traffic_lingbot_pmc.txt for the commands
-MEASURED_ATTENTION_TRAFFIC = {2: (2 * 654284 + 46800) * 1024}
+MEASURED_ATTENTION_TRAFFIC = {2: (2 * 700460 + 46800) * 1024}
 # shader clock the chip holds while the attention kernel runs (SQ_BUSY_CYCLES over the kernel's duration in the
 # same counter runs); the peak at that clock is 256 CUs x 4 SIMDs x 1,024 bf16 flop per cycle
 MEASURED_ATTENTION_CLOCK_GHZ = {2: 1.76}

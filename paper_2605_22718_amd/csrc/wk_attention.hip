@@ -356,6 +356,8 @@ __device__ inline float max_across_halves(float x) {
     "v244", "v245", "v246"
 
 #define WK_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+// typed LDS pointer from a 32-bit LDS byte address
+#define WK_LDS_AT(T, addr) ((__attribute__((address_space(3))) T *)(size_t)(addr))
 #define WK_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
 
 // IN_PLACE: the window is a list of segments (the native rows, then each retrieved chunk where the store
@@ -470,21 +472,23 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
 
     // K tile: row-major, chunk c of key k at slot c ^ (k & 15).  A operand of S^T block b, step st:
     // key 32*b + col, chunk 2*st + g.   address = k_rd[st] + stage*16384 + b*8192
-    const char *k_rd[8];
+    // (operand read addresses are kept as 32-bit LDS addresses: the hand-scheduled loop takes them as they are)
+    const unsigned lds0 = (unsigned)(size_t)WK_LDS(smem);
+    unsigned k_rd[8];
 #pragma unroll
-    for (int st = 0; st < 8; ++st) k_rd[st] = smem + col * 256 + (((2 * st + g) ^ (col & 15)) << 4);
+    for (int st = 0; st < 8; ++st) k_rd[st] = lds0 + col * 256 + (((2 * st + g) ^ (col & 15)) << 4);
     // V tile: row-major, chunk c of key k at slot c ^ ((k & 3) << 2).  The transpose read hands lane
     // i of a 16-lane group element (i & 3) of source lane 4*j + (i >> 2), j = 0..3.  Source lane p of
     // group u points at key 16*ks + 8*tt + 4*g + (p >> 2), features 32*blk + 16*(u&1) + 4*(p&3) .. +3,
     // so lane i receives feature 32*blk + 16*(u&1) + i of keys 16*ks + 8*tt + 4*g + 0..3: the four
     // k slots that registers 4*tt .. 4*tt+3 of the P^T operand of step ks stand for.
     //   address = v_rd[blk] + stage*16384 + ks*4096 + tt*2048
-    const char *v_rd[4];
+    unsigned v_rd[4];
     {
         const int u = lane >> 4, p = lane & 15;
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk)
-            v_rd[blk] = smem + kVRing + (4 * g + (p >> 2)) * 256 +
+            v_rd[blk] = lds0 + kVRing + (4 * g + (p >> 2)) * 256 +
                         ((4 * (blk ^ (p >> 2)) + 2 * (u & 1) + ((p & 3) >> 1)) << 4) + 8 * (p & 1);
     }
     // tile loads: wave w fills 1 KB blocks NB*w .. NB*w + NB-1 of the K tile and of the V tile; lane l
@@ -516,7 +520,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     const char *cur_k = nullptr, *cur_v = nullptr;
     int cur_len = 0, cur_row = 0, cur_seg = 0;
     TileRef v_line[2] = {{nullptr, 0, 0}, {nullptr, 0, 0}};
-    int valid_line[4] = {0, 0, 0, 0};
+    unsigned valid_line = 0;   // four entries of 8 bits, newest lowest: valid keys of a tile, capped at 64 (scalar registers are scarce here)
     if constexpr (IN_PLACE) {
         if (n_seg > 0) {
             cur_len = __builtin_amdgcn_readfirstlane(seg_list[0].len);
@@ -544,10 +548,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         issue_at(cur_k, cur_row, cur_len, k_src, dst);
         v_line[1] = v_line[0];
         v_line[0] = TileRef{cur_v, cur_row, cur_len};
-        valid_line[3] = valid_line[2];
-        valid_line[2] = valid_line[1];
-        valid_line[1] = valid_line[0];
-        valid_line[0] = cur_len - cur_row;   // 64 or more: a full tile
+        valid_line = (valid_line << 8) | (unsigned)min(cur_len - cur_row, kKeys);   // 64: a full tile
         if (cur_row + kKeys < cur_len) {
             cur_row += kKeys;
         } else if (cur_seg + 1 < n_seg) {
@@ -605,7 +606,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     float m_run = -INFINITY, l_run = 0.f;   // m_run in scaled (log2) units
     const float c_log2 = a.scale_log2;
 
-    auto compute_s = [&](int byte_off, f32x16 (&s)[2]) {
+    auto compute_s = [&](int byte_off, f32x16 (&s)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -615,14 +616,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         for (int st = 0; st < 8; ++st)
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(k_rd[st] + byte_off + b * 8192);
+                const bf16x8 ka = *WK_LDS_AT(const bf16x8, k_rd[st] + byte_off + b * 8192);
                 s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[st], s[b], 0, 0, 0);
             }
     };
     // IN_PLACE: the tile whose S^T has just been formed had its K tile requested three requests ago; keys
     // past its segment's end get -inf (weight exactly 0).
-    auto mask_segment_tail = [&](f32x16 (&s)[2]) {
-        const int valid = valid_line[3];
+    auto mask_segment_tail = [&](f32x16 (&s)[2]) __attribute__((always_inline)) {
+        const int valid = (int)(valid_line >> 24);
         if (valid < kKeys) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
@@ -632,7 +633,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         }
     };
     // scaled row max of a tile's raw logits (both lane halves combined)
-    auto tile_max = [&](const f32x16 (&s)[2]) {
+    auto tile_max = [&](const f32x16 (&s)[2]) __attribute__((always_inline)) {
         float mx[10];
 #pragma unroll
         for (int i = 0; i < 10; ++i) {
@@ -644,7 +645,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         return max_across_halves(m) * c_log2;
     };
     // lazy rescale: the running max only moves when some row's max grew by more than 2^8
-    auto maybe_rescale = [&](float m_tile) {
+    auto maybe_rescale = [&](float m_tile) __attribute__((always_inline)) {
         if (__any(m_tile > m_run + 8.0f)) {
             const float m_new = fmaxf(m_run, m_tile);
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -658,7 +659,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     };
     // p = exp2(s*c - m) rounded to bf16; registers 8*t2 .. 8*t2+7 of block b -> k step 2*b + t2.
     // The row sum uses the rounded probabilities, the ones the P V product sees.
-    auto probabilities = [&](const f32x16 (&s)[2], bf16x8 (&pb)[4]) {
+    auto probabilities = [&](const f32x16 (&s)[2], bf16x8 (&pb)[4]) __attribute__((always_inline)) {
         const float neg_m = -m_run;
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
@@ -675,33 +676,32 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
                     l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
                 }
     };
-    auto accumulate_pv = [&](int byte_off, const bf16x8 (&pb)[4]) {
+    auto accumulate_pv = [&](int byte_off, const bf16x8 (&pb)[4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const char *p = v_rd[b] + byte_off + ks * 4096;
-                const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p));
-                const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 2048));
+                const unsigned p = v_rd[b] + byte_off + ks * 4096;
+                const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(WK_LDS_AT(i16x4, p));
+                const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(WK_LDS_AT(i16x4, p + 2048));
                 const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[ks], o[b], 0, 0, 0);
             }
     };
 
-    // The ring slot of tile j is (j + sh) & 3 with sh chosen so that the last tile sits in slot 0:
-    // the 4-step unrolled loop below is entered at position sh and always ends on a full group.
+    // The ring slot of tile j is j & 3.  Whole groups of four steps come first (the steady state), then the
+    // n_steps & 3 left-over steps, then the last tile at whatever ring position that leaves it.
     const int n_steps = t1 - t0 - 1;
-    const int sh = (4 - (n_steps & 3)) & 3;
     // Step j multiplies K tile j+1 (S^T one step early) and V tile j, so K runs one tile ahead of V:
     // step j loads K tile j+4 into the slot of K tile j (read in step j-1) and V tile j+3 into the slot
     // of V tile j-1.  Both then have three steps to land before the step that needs them.
-    issue_k(0, sh);
-    issue_k(1, (sh + 1) & 3);
-    issue_v(0, sh);
-    issue_k(2, (sh + 2) & 3);
-    issue_v(1, (sh + 1) & 3);
-    issue_k(3, (sh + 3) & 3);
-    issue_v(2, (sh + 2) & 3);
+    issue_k(0, 0);
+    issue_k(1, 1);
+    issue_v(0, 0);
+    issue_k(2, 2);
+    issue_v(1, 1);
+    issue_k(3, 3);
+    issue_v(2, 2);
     __builtin_amdgcn_s_waitcnt(kWaitTwoSteps);   // K tiles 0, 1 and V tile 0 of this wave have landed
     __syncthreads();
     if (qt * (WAVES * 32) + wave * 32 >= a.N_q) {
@@ -710,8 +710,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         // SIMD to the wave that has work.
         __syncthreads();   // the others' first S^T has been formed from K tile 0
         for (int j = 0; j < n_steps; ++j) {
-            issue_k(j + 4, (j + sh) & 3);
-            issue_v(j + 3, (j + sh + 3) & 3);
+            issue_k(j + 4, j & 3);
+            issue_v(j + 3, (j + 3) & 3);
             __builtin_amdgcn_s_waitcnt(kWaitTwoSteps);
             __syncthreads();
         }
@@ -720,20 +720,13 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
     }
     f32x16 s_a[2], s_b[2];   // S^T of tiles at even / odd ring positions
     float mt;
-    if (sh & 1) {
-        compute_s(sh * kTileBytes, s_b);
-        if constexpr (IN_PLACE) mask_segment_tail(s_b);
-        mt = tile_max(s_b);
-    } else {
-        compute_s(sh * kTileBytes, s_a);
-        if constexpr (IN_PLACE) mask_segment_tail(s_a);
-        mt = tile_max(s_a);
-    }
+    compute_s(0, s_a);
+    if constexpr (IN_PLACE) mask_segment_tail(s_a);
+    mt = tile_max(s_a);
     __syncthreads();   // K tile 0 has been read by every wave: step 0 may load K tile 4 into its slot
 
     // one pipeline step: tile j (ring position POS) is consumed, S^T of tile j+1 produced
-    auto step = [&](int j, auto pos_tag, f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) {
-        constexpr int POS = decltype(pos_tag)::value;
+    auto step = [&](int j, const int POS, f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) __attribute__((always_inline)) {
         issue_k(j + 4, POS);
         issue_v(j + 3, (POS + 3) & 3);
         maybe_rescale(mt);
@@ -748,32 +741,18 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
         __builtin_amdgcn_s_waitcnt(kWaitTwoSteps);   // all but the loads of this step and the one before have landed
         __syncthreads();
     };
-    using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
-    using P2 = std::integral_constant<int, 2>;
-    using P3 = std::integral_constant<int, 3>;
     int j = 0;
-    if (n_steps > 0) {   // partial first group: positions sh .. 3
-        if (sh == 1) { step(j++, P1{}, s_b, s_a); step(j++, P2{}, s_a, s_b); step(j++, P3{}, s_b, s_a); }
-        else if (sh == 2) { step(j++, P2{}, s_a, s_b); step(j++, P3{}, s_b, s_a); }
-        else if (sh == 3) { step(j++, P3{}, s_b, s_a); }
-    }
-    if constexpr (WAVES == 8 && !MULTI && !IN_PLACE) {
+    if constexpr (WAVES == 8 && !IN_PLACE) {
         // Steady state: whole groups of four steps whose look-ahead loads all lie inside the window run in the
         // hand-scheduled loop of wk_attn_loop_gfx950.inc (written by gen_attn_loop.py, which documents its schedule
         // and register map).  It is the four `step`s below instruction for instruction in what it computes -- same
-        // ring protocol, same arithmetic in the same order, bit-identical results -- so the steps before and behind
-        // it stay in C++: the partial first group, the last steps, whose loads are clamped to the window, and the
+        // ring protocol, same arithmetic in the same order, bit-identical results -- so the steps behind it
+        // stay in C++: the last whole groups, whose loads are clamped to the window, the left-over steps and the
         // last, possibly partial tile.  Its operands are pinned to the registers its text names.
         int G = (n_kv / kKeys - 4 - t0 - j) / 4;
         const int G_steps = (n_steps - j) / 4;
         G = G < G_steps ? G : G_steps;
         if (G > 0) {
-            unsigned ad[12];
-#pragma unroll
-            for (int st = 0; st < 8; ++st) ad[st] = (unsigned)(size_t)WK_LDS(k_rd[st]);
-#pragma unroll
-            for (int b = 0; b < 4; ++b) ad[8 + b] = (unsigned)(size_t)WK_LDS(v_rd[b]);
             const unsigned koff = (unsigned)(t0 + j + 4) * (kKeys * 256u), voff = (unsigned)(t0 + j + 3) * (kKeys * 256u);
             const unsigned dst = (unsigned)(size_t)WK_LDS(dma_dst);
             int g_left = G;
@@ -785,9 +764,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
                 : "+{v[0:15]}"(o0), "+{v[16:31]}"(o1), "+{v[32:47]}"(o2), "+{v[48:63]}"(o3), "+{v[64:79]}"(sa0),
                   "+{v[80:95]}"(sa1), "+{v240}"(m_run), "+{v241}"(l_run), "+{v243}"(mt), "+{s44}"(g_left)
                 : "{v[128:131]}"(q0), "{v[132:135]}"(q1), "{v[136:139]}"(q2), "{v[140:143]}"(q3), "{v[144:147]}"(q4),
-                  "{v[148:151]}"(q5), "{v[152:155]}"(q6), "{v[156:159]}"(q7), "{v224}"(ad[0]), "{v225}"(ad[1]),
-                  "{v226}"(ad[2]), "{v227}"(ad[3]), "{v228}"(ad[4]), "{v229}"(ad[5]), "{v230}"(ad[6]), "{v231}"(ad[7]),
-                  "{v232}"(ad[8]), "{v233}"(ad[9]), "{v234}"(ad[10]), "{v235}"(ad[11]), "{v236}"(ks0), "{v237}"(ks1),
+                  "{v[148:151]}"(q5), "{v[152:155]}"(q6), "{v[156:159]}"(q7), "{v224}"(k_rd[0]), "{v225}"(k_rd[1]),
+                  "{v226}"(k_rd[2]), "{v227}"(k_rd[3]), "{v228}"(k_rd[4]), "{v229}"(k_rd[5]), "{v230}"(k_rd[6]), "{v231}"(k_rd[7]),
+                  "{v232}"(v_rd[0]), "{v233}"(v_rd[1]), "{v234}"(v_rd[2]), "{v235}"(v_rd[3]), "{v236}"(ks0), "{v237}"(ks1),
                   "{v238}"(vs0), "{v239}"(vs1), "{s[36:37]}"(Kh), "{s[38:39]}"(Vh), "{s40}"(koff), "{s41}"(voff),
                   "{s42}"(dst), "{s43}"(c_log2)
                 : WK_ATTN_LOOP_CLOBBERS, "s45", "vcc", "memory");
@@ -795,15 +774,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
             j += 4 * G;
         }
     }
-    for (; j < n_steps; j += 4) {
-        step(j, P0{}, s_a, s_b);
-        step(j + 1, P1{}, s_b, s_a);
-        step(j + 2, P2{}, s_a, s_b);
-        step(j + 3, P3{}, s_b, s_a);
+    for (; j + 4 <= n_steps; j += 4) {
+        step(j, 0, s_a, s_b);
+        step(j + 1, 1, s_b, s_a);
+        step(j + 2, 2, s_a, s_b);
+        step(j + 3, 3, s_b, s_a);
     }
-    // last tile (ring position 0, S^T in s_a): the only one that can be partial.  Mask the keys
-    // past the window and redo its max.
-    {
+    // last tile (ring position POS): the only one that can be partial.  Mask the keys past the window and
+    // redo its max.
+    auto last_tile = [&](const int POS, f32x16 (&s_cur)[2]) __attribute__((always_inline)) {
         const int kt = (t1 - 1) * kKeys;
         if (!IN_PLACE && kt + kKeys > n_kv) {
 #pragma unroll
@@ -811,15 +790,23 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_attn_bf16(AttnArgs a, SubTabl
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = kt + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (key >= n_kv) s_a[b][r] = -INFINITY;
+                    if (key >= n_kv) s_cur[b][r] = -INFINITY;
                 }
-            mt = tile_max(s_a);
+            mt = tile_max(s_cur);
         }
         maybe_rescale(mt);
         bf16x8 pb[4];
-        probabilities(s_a, pb);
-        accumulate_pv(0, pb);
+        probabilities(s_cur, pb);
+        accumulate_pv(POS * kTileBytes, pb);
+    };
+    // the n_steps & 3 left-over steps and the last tile: one copy of the code, ring position at run time,
+    // S^T handed back to s_a after each step
+    for (; j < n_steps; ++j) {
+        step(j, j & 3, s_a, s_b);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) s_a[b] = s_b[b];
     }
+    last_tile(n_steps & 3, s_a);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the clamped look-ahead loads before the LDS is released
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
