@@ -53,6 +53,18 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+DRIVER_SRC = os.path.join(HERE, "profile_driver", "wk_profile_driver.cpp")
+DRIVER = os.path.join(HERE, "profile_driver", "wk_profile_driver")
+
+
+def build_profile_driver() -> str:
+    """The torch-free program the hardware-counter profiles are taken on (host code only; it calls libwk.so)."""
+    subprocess.run([HIPCC, "-O2", "-std=c++17", "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"),
+                    "-I", "/opt/rocm/include", DRIVER_SRC, "-o", DRIVER, "-L", HERE, "-lwk", "-L", "/opt/rocm/lib", "-lamdhip64",
+                    "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    return DRIVER
+
+
 SAN_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
             "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
 
