@@ -29,9 +29,11 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # scaled by what the counter reads for the plain calibration copy (0.500 and 1.000), per workload index;
 # see profiles/hbm_traffic_lingbot_pmc.txt for the commands
 MEASURED_ATTENTION_TRAFFIC = {2: (2 * 700460 + 46800) * 1024}
-# shader clock the chip holds while the attention kernel runs (SQ_BUSY_CYCLES over the kernel's duration in the
-# same counter runs); the peak at that clock is 256 CUs x 4 SIMDs x 1,024 bf16 flop per cycle
-MEASURED_ATTENTION_CLOCK_GHZ = {2: 1.76}
+# shader-clock cycles one wk_attention launch on this workload takes (SQ_BUSY_CYCLES over the 32 shader engines in
+# the counter runs of profiles/hbm_traffic_lingbot_pmc.txt): a property of the kernel and the workload, while the
+# clock the chip holds under this load differs from box to box.  The clock reported beside the roofline is this
+# count over the launch time measured here; the peak at that clock is 256 CUs x 4 SIMDs x 1,024 bf16 flop per cycle.
+MEASURED_ATTENTION_CYCLES = {2: 3.848e6}
 FLOP_PER_CLOCK = 256 * 4 * 1024
 
 
@@ -456,7 +458,8 @@ def main():
         torch.cuda.synchronize()
         del pstore, pk, pv
 
-    clk = MEASURED_ATTENTION_CLOCK_GHZ.get(cfg.index)
+    cycles = MEASURED_ATTENTION_CYCLES.get(cfg.index)
+    clk = cycles / (att_ms * 1e-3) / 1e9 if cycles else None
     value = flops / (ms_step * 1e-3) / 1e12
     out = {
         "metric": "attention TFLOP/s of the whole hot-path step (4*N_q*N_kv*d*H flop of wk_attention over the time "

@@ -283,8 +283,12 @@ __global__ __launch_bounds__(512, 2) void k_score_gemm(const char *__restrict__ 
         // the last anchor block, where the groups of pure padding are skipped (their weights are 0 anyway)
         const int rows_left = p.T - (ab * kGemmTile + 128 * wa);
         const int mb_valid = rows_left >= 128 ? 4 : (rows_left <= 0 ? 0 : (rows_left + 31) / 32);
-        auto contract = [&](auto mv_tag) {
-            constexpr int MV = decltype(mv_tag)::value;
+        // likewise the wave's two 32-candidate blocks: past the last candidate (last candidate tile) nothing
+        // is multiplied
+        const int cols_left = p.n_cand - (j0 + 64 * wc);
+        const int nb_valid = cols_left >= 64 ? 2 : (cols_left <= 0 ? 0 : (cols_left + 31) / 32);
+        auto contract = [&](auto mv_tag, auto nv_tag) {
+            constexpr int MV = decltype(mv_tag)::value, NV = decltype(nv_tag)::value;
             for (int step = 0; step < n_steps; ++step) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of the step's tiles has landed
                 __syncthreads();                      // everyone's has, and the other stage is free again
@@ -293,29 +297,38 @@ __global__ __launch_bounds__(512, 2) void k_score_gemm(const char *__restrict__ 
                 if constexpr (MV > 0) {
 #pragma unroll
                     for (int st = 0; st < 4; ++st) {
-                        bf16x8 fa[MV], fb[2];
+                        bf16x8 fa[MV], fb[NV];
 #pragma unroll
                         for (int mb = 0; mb < MV; ++mb)
                             fa[mb] = *reinterpret_cast<const bf16x8 *>(a_rd[st] + off + mb * 4096);
 #pragma unroll
-                        for (int nb = 0; nb < 2; ++nb)
+                        for (int nb = 0; nb < NV; ++nb)
                             fb[nb] = *reinterpret_cast<const bf16x8 *>(b_rd[st] + off + nb * 4096);
 #pragma unroll
                         for (int mb = 0; mb < MV; ++mb)
 #pragma unroll
-                            for (int nb = 0; nb < 2; ++nb)
+                            for (int nb = 0; nb < NV; ++nb)
                                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[nb], acc[mb][nb], 0, 0, 0);
                     }
                 }
             }
         };
         if (n_steps > 0) issue(0, 0);
-        switch (mb_valid) {   // wave-uniform; every variant passes the same barriers
-        case 4: contract(std::integral_constant<int, 4>{}); break;
-        case 3: contract(std::integral_constant<int, 3>{}); break;
-        case 2: contract(std::integral_constant<int, 2>{}); break;
-        case 1: contract(std::integral_constant<int, 1>{}); break;
-        default: contract(std::integral_constant<int, 0>{}); break;
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        using I3 = std::integral_constant<int, 3>;
+        using I4 = std::integral_constant<int, 4>;
+        switch (nb_valid == 0 ? 0 : 2 * mb_valid + nb_valid - 1) {   // wave-uniform; every variant passes the same barriers
+        case 9: contract(I4{}, I2{}); break;
+        case 8: contract(I4{}, I1{}); break;
+        case 7: contract(I3{}, I2{}); break;
+        case 6: contract(I3{}, I1{}); break;
+        case 5: contract(I2{}, I2{}); break;
+        case 4: contract(I2{}, I1{}); break;
+        case 3: contract(I1{}, I2{}); break;
+        case 2: contract(I1{}, I1{}); break;
+        default: contract(I0{}, I0{}); break;
         }
         // fold the block in: accumulator register r of block mb is anchor 128*wa + 32*mb + 8*(r/4) + 4*gh + r%4
         // (an empty head range has passed no barrier since the weights were written, and has nothing to add)
