@@ -261,7 +261,21 @@ def main():
     cal_dst = torch.zeros_like(Kw)          # written after cal_src: pushes it out of the Infinity Cache
     wk.wk_calibration_copy(cal_dst, cal_src)
     del cal_src, cal_dst
+    # context for the attention roofline: what the vendor library's dense bf16 GEMM reaches on this machine, on N(0,1)
+    # operands like the window's (the chip is power-limited under dense matrix work, so no kernel holds the
+    # nameplate peak; this is a measured reference, not the roofline's `peak`)
+    gemm_tflops = None
+    if cfg.dtype == ws.configs.DT_BF16:
+        n_g = 8192
+        ga = torch.randn(n_g, n_g, device=dev, dtype=torch.bfloat16)
+        gb = torch.randn(n_g, n_g, device=dev, dtype=torch.bfloat16)
+        gc = torch.empty(n_g, n_g, device=dev, dtype=torch.bfloat16)
+        t_gemm = min(time_call(lambda: torch.matmul(ga, gb, out=gc), reps),
+                     time_call(lambda: torch.matmul(ga, gb.t(), out=gc), reps))   # B row-major / B transposed
+        gemm_tflops = 2.0 * n_g ** 3 / (t_gemm * 1e-3) / 1e12
+        del ga, gb, gc
     extra = {
+        "library_gemm_bf16_8192_tflops": gemm_tflops,
         "d2d_copy_ceiling_GBps": 2 * flat.numel() * flat.element_size() / (t_d2d * 1e-3) / 1e9,
         "attention_tflops": att_tflops,
         "pct_bf16_mfma_peak": 100.0 * att_tflops / PEAK_BF16_TFLOPS,
