@@ -139,6 +139,20 @@ def test_more_items_than_compute_units_with_and_without_workspace(H, Nq, Nkv, n_
     _check(Q, K, V, O, lse, N_kv=Nkv if n_dev is None else n_dev, rows=rows)
 
 
+@pytest.mark.parametrize("Nkv", [1024, 1100, 1160, 1217, 1285, 1344, 2049])
+def test_eight_wave_loop_every_ring_phase(Nkv):
+    """A grid that takes the 256-query workgroups (32 heads x 8 query tiles), windows of 16 .. 33 tiles: the
+    hand-scheduled groups of four steps are followed by 3, 1, 2, 3, 0, 0 and 0 left-over steps, the last tile is
+    whole or ragged, and every ring position holds the last tile once."""
+    H, Nq = 32, 2048
+    Q, K, V = _rand(H, Nq, Nkv, torch.bfloat16, seed=7 * Nkv)
+    O, lse = _run(Q, K, V, split=False)
+    assert not torch.isnan(O.float()).any() and not torch.isnan(lse).any()
+    rng = np.random.default_rng(Nkv)
+    rows = sorted(set([0, 31, 32, 255, 256, Nq - 1] + rng.integers(0, Nq, 42).tolist()))
+    _check(Q, K, V, O, lse, rows=rows, full_size=True)
+
+
 @pytest.mark.parametrize("case", ["overflow", "underflow", "mixed"])
 def test_logits_far_outside_the_range_of_exp2(case):
     """Rows whose logits reach the hundreds, or lie far below zero for every key, or both kinds of row in one
