@@ -65,6 +65,19 @@ def build_profile_driver() -> str:
     return DRIVER
 
 
+PROBE_SRC = os.path.join(HERE, "profile_driver", "wk_mfma_duty_probe.hip")
+PROBE = os.path.join(HERE, "profile_driver", "wk_mfma_duty_probe")
+
+
+def build_mfma_duty_probe() -> str:
+    """The matrix-instruction duty probe (clock and rate of bare bf16 MFMA loops): a program of its own, no libwk."""
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", PROBE_SRC, "-o", PROBE], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {PROBE_SRC}:\n{r.stderr}")
+    return PROBE
+
+
 SAN_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
             "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
 
