@@ -270,9 +270,10 @@ def main():
         ga = torch.randn(n_g, n_g, device=dev, dtype=torch.bfloat16)
         gb = torch.randn(n_g, n_g, device=dev, dtype=torch.bfloat16)
         gc = torch.empty(n_g, n_g, device=dev, dtype=torch.bfloat16)
-        t_gemm = min(time_call(lambda: torch.matmul(ga, gb, out=gc), reps),
-                     time_call(lambda: torch.matmul(ga, gb.t(), out=gc), reps))   # B row-major / B transposed
-        gemm_tflops = 2.0 * n_g ** 3 / (t_gemm * 1e-3) / 1e12
+        gemm_tflops = {   # B given row-major (k x n) / as the transpose of a row-major n x k matrix
+            "b_row_major": 2.0 * n_g ** 3 / (time_call(lambda: torch.matmul(ga, gb, out=gc), reps) * 1e-3) / 1e12,
+            "b_transposed": 2.0 * n_g ** 3 / (time_call(lambda: torch.matmul(ga, gb.t(), out=gc), reps) * 1e-3) / 1e12,
+        }
         del ga, gb, gc
     extra = {
         "library_gemm_bf16_8192_tflops": gemm_tflops,

@@ -127,6 +127,127 @@ __global__ __launch_bounds__(WK_D) void k_anchor_mean_finish(const double *__res
     m[bh * WK_D + threadIdx.x] = (float)(s / (double)p.T);
 }
 
+// Anchor norms and the normalised anchor mean in ONE pass over the anchor rows, for head-shared lists (a token's
+// norm runs over all heads, so a wave takes whole tokens): each of the workgroup's four waves walks
+// tok_per_wave anchor tokens; per token it requests the token's rows of all heads at once (head h goes to
+// 16-lane group h & 3, IT >= ceil(H / 4) rows per group), sums their squares across the wave in fp64 and adds
+// row / |k_i| to per-lane fp32 sums (at most 32 terms of magnitude <= 1: the rounding stays below 1e-10 of the
+// scores).  The four waves' sums meet through LDS in a fixed order, and one workgroup writes one partial sum per
+// (head, feature); k_anchor_mean_fold adds the partials in fp64.  The separate norm pass and its buffer are gone.
+constexpr int kFuseWaves = 4;
+
+template <int DT, int IT>
+__global__ __launch_bounds__(kFuseWaves * 64) void k_anchor_norm_mean(const char *__restrict__ A, CompressDims p,
+                                                                      int tok_per_wave, int n_splits,
+                                                                      float *__restrict__ partial) {
+    extern __shared__ __attribute__((aligned(16))) float fuse_red[];   // [kFuseWaves][H][128]
+    const int split = blockIdx.x, b = blockIdx.z;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int q = lane >> 4, sub = lane & 15;
+    const size_t row_bytes = WK_D * wk::esize(DT);
+    const size_t head_bytes = (size_t)p.a_rows * row_bytes;
+    const char *base = A + (size_t)b * p.H * head_bytes;
+    float acc[IT][8];
+#pragma unroll
+    for (int it = 0; it < IT; ++it)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[it][e] = 0.f;
+    const int i0 = (split * kFuseWaves + wave) * tok_per_wave;
+    const int i1 = min(p.T, i0 + tok_per_wave);
+    // rows stay as loaded (16 bytes per lane and row, bf16; 32 bytes, fp32) until they are used, and the next
+    // token's rows are requested before the current token's are reduced
+    constexpr int kVec = DT == WK_BF16 ? 1 : 2;
+    uint4 cur[IT][kVec], nxt[IT][kVec];
+    auto request = [&](int i, uint4 (&dst)[IT][kVec]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int h = 4 * it + q;
+            const uint4 *row = reinterpret_cast<const uint4 *>(base + (size_t)(h < p.H ? h : 0) * head_bytes + (size_t)i * row_bytes);
+#pragma unroll
+            for (int u = 0; u < kVec; ++u) dst[it][u] = h < p.H ? row[kVec * sub + u] : uint4{0, 0, 0, 0};
+        }
+    };
+    auto unpack = [&](const uint4 (&src)[kVec], float (&v)[8]) __attribute__((always_inline)) {
+        if constexpr (DT == WK_BF16) {
+            const uint32_t w[4] = {src[0].x, src[0].y, src[0].z, src[0].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                v[2 * k] = __uint_as_float(w[k] << 16);
+                v[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+            }
+        } else {
+            const uint32_t w[8] = {src[0].x, src[0].y, src[0].z, src[0].w, src[kVec - 1].x, src[kVec - 1].y, src[kVec - 1].z, src[kVec - 1].w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = __uint_as_float(w[k]);
+        }
+    };
+    if (i0 < i1) request(i0, cur);
+    for (int i = i0; i < i1; ++i) {
+        if (i + 1 < i1) request(i + 1, nxt);
+        double n2 = 0.0;
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            float v[8];
+            unpack(cur[it], v);
+            float sq = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sq = fmaf(v[e], v[e], sq);
+            n2 += (double)sq;
+        }
+        n2 = wk::row_group_sum(n2);
+        n2 += __shfl_xor(n2, 16);
+        n2 += __shfl_xor(n2, 32);
+        const float rn = n2 < 1e-60 ? 0.f : (float)(1.0 / sqrt(n2));   // zero-norm key: its cosines are 0
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            float v[8];
+            unpack(cur[it], v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[it][e] = fmaf(v[e], rn, acc[it][e]);
+        }
+#pragma unroll
+        for (int it = 0; it < IT; ++it)
+#pragma unroll
+            for (int u = 0; u < kVec; ++u) cur[it][u] = nxt[it][u];
+    }
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+        const int h = 4 * it + q;
+        if (h < p.H) {
+            float *dst = fuse_red + ((size_t)wave * p.H + h) * WK_D + 8 * sub;
+            *reinterpret_cast<float4 *>(dst) = float4{acc[it][0], acc[it][1], acc[it][2], acc[it][3]};
+            *reinterpret_cast<float4 *>(dst + 4) = float4{acc[it][4], acc[it][5], acc[it][6], acc[it][7]};
+        }
+    }
+    __syncthreads();
+    const int n = p.H * WK_D;
+    for (int idx = threadIdx.x; idx < n; idx += kFuseWaves * 64) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kFuseWaves; ++w) t += (double)fuse_red[(size_t)w * n + idx];
+        const int h = idx / WK_D, c = idx % WK_D;
+        partial[(((size_t)b * p.H + h) * n_splits + split) * WK_D + c] = (float)t;
+    }
+}
+
+// m[(b*H+h)*128 + c] = (1/T) sum over the n_splits partial sums of k_anchor_norm_mean, in fp64 and in a fixed order
+__global__ __launch_bounds__(WK_D) void k_anchor_mean_fold(const float *__restrict__ partial, CompressDims p, int n_splits,
+                                                          float *__restrict__ m) {
+    const size_t bh = (size_t)blockIdx.y * p.H + blockIdx.x;
+    const float *src = partial + bh * n_splits * WK_D + threadIdx.x;
+    double s = 0.0;
+    int sp = 0;
+    for (; sp + 8 <= n_splits; sp += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = src[(size_t)(sp + u) * WK_D];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)t[u];
+    }
+    for (; sp < n_splits; ++sp) s += (double)src[(size_t)sp * WK_D];
+    m[bh * WK_D + threadIdx.x] = (float)(s / (double)p.T);
+}
+
 // scores[(b*G+g)*n_cand + j] = (k_j . m) / |k_j|
 template <int DT, int HS>
 __global__ __launch_bounds__(256) void k_score_factored(const char *__restrict__ K, CompressDims p,
@@ -525,6 +646,24 @@ struct WsLayout {
     size_t scores, nsq, nsq_cand, gemm_partial, mean, mean_partial, kept, total;
 };
 
+// The one-pass anchor kernel serves factored scoring with head-shared lists of up to 64 heads in batches large
+// enough that a wave walks 8 to 32 tokens (a single LingBot-sized chunk would have to give each wave 4 tokens to
+// spread over the chip at all, and that dependent chain is slower than the two separate passes: 65 against 52 us
+// for the whole call).
+struct FusePlan { bool use; int tok_per_wave, n_splits, it; };
+
+FusePlan fuse_plan(const wk_compress_desc *d, const CompressDims &p) {
+    FusePlan f{false, 0, 0, 0};
+    if (d->score_algo != WK_SCORE_FACTORED || p.G != 1 || p.H > 64) return f;
+    const long long tpw = ((long long)p.T * d->batch + 4095) / 4096;
+    if (tpw < 8) return f;   // too few tokens to keep every wave on a long run of them: the two short passes win
+    f.use = true;
+    f.tok_per_wave = (int)(tpw > 32 ? 32 : tpw);
+    f.n_splits = (p.T + kFuseWaves * f.tok_per_wave - 1) / (kFuseWaves * f.tok_per_wave);
+    f.it = p.H <= 12 ? 3 : (p.H <= 40 ? 10 : 16);
+    return f;
+}
+
 bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
     if (!d || d->H < 1 || d->T < 1 || d->F < 1 || d->batch < 1) return false;
     int32_t n_out = 0, n_keep = 0;
@@ -555,7 +694,12 @@ bool make_dims(const wk_compress_desc *d, CompressDims &p, WsLayout &ws) {
     }
     ws.mean = off;   off = wk::align_up(off + (size_t)d->batch * d->H * WK_D * sizeof(float), 256);
     ws.mean_partial = off;
-    off = wk::align_up(off + (size_t)d->batch * d->H * kMeanSplits * WK_D * sizeof(double), 256);
+    {
+        const size_t two_pass = (size_t)d->batch * d->H * kMeanSplits * WK_D * sizeof(double);
+        const FusePlan fp = fuse_plan(d, p);
+        const size_t fused = fp.use ? (size_t)d->batch * d->H * fp.n_splits * WK_D * sizeof(float) : 0;
+        off = wk::align_up(off + (two_pass > fused ? two_pass : fused), 256);
+    }
     ws.kept = off;   off = wk::align_up(off + lists * (size_t)n_out * sizeof(int32_t), 256);
     ws.total = off;
     return true;
@@ -575,6 +719,37 @@ wk_status check_desc(const wk_compress_desc *d) {
     return WK_OK;
 }
 
+// k_anchor_norm_mean for the plan's rows-per-group count; its LDS (four waves' sums of H x 128 floats) can exceed
+// the default 64 KB of dynamic LDS, so the limit is raised once per device and instantiation.
+template <int DT, int IT>
+wk_status launch_norm_mean_it(const FusePlan &f, const char *A, const CompressDims &p, int batch, float *partial,
+                              hipStream_t st) {
+    const size_t lds = (size_t)kFuseWaves * p.H * WK_D * sizeof(float);
+    static std::atomic<uint64_t> lds_limit_set{0};
+    int dev;
+    if (wk::device_needs_setup(lds_limit_set, dev)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_anchor_norm_mean<DT, IT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kFuseWaves * 64 * WK_D * (int)sizeof(float)) !=
+            hipSuccess)
+            return WK_ERR_HIP;
+        wk::mark_device(lds_limit_set, dev);
+    }
+    hipLaunchKernelGGL((k_anchor_norm_mean<DT, IT>), dim3(f.n_splits, 1, batch), dim3(kFuseWaves * 64), lds, st, A, p,
+                       f.tok_per_wave, f.n_splits, partial);
+    WK_LAUNCH_CHECK();
+    return WK_OK;
+}
+
+template <int DT>
+wk_status launch_norm_mean(const FusePlan &f, const char *A, const CompressDims &p, int batch, float *partial,
+                           hipStream_t st) {
+    switch (f.it) {
+    case 3: return launch_norm_mean_it<DT, 3>(f, A, p, batch, partial, st);
+    case 10: return launch_norm_mean_it<DT, 10>(f, A, p, batch, partial, st);
+    default: return launch_norm_mean_it<DT, 16>(f, A, p, batch, partial, st);
+    }
+}
+
 template <int DT>
 wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsLayout &ws, const void *K,
                      const void *V, const void *K_anchor, int32_t *kept_idx, void *K_out, void *V_out,
@@ -590,10 +765,13 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
         // 16-lane groups), otherwise 16 lanes per token
         const bool split = p.hg >= 4;
         const int rows_pb = split ? kRowsPerBlock / 4 : kRowsPerBlock;
-        dim3 g1((p.T + rows_pb - 1) / rows_pb, p.G, d->batch);
-        if (split) hipLaunchKernelGGL((k_rows_normsq<DT, 4>), g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
-        else hipLaunchKernelGGL((k_rows_normsq<DT, 1>), g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
-        WK_LAUNCH_CHECK();
+        const FusePlan fuse = fuse_plan(d, p);
+        if (!fuse.use) {   // squared norms of the anchor tokens, a pass of their own
+            dim3 g1((p.T + rows_pb - 1) / rows_pb, p.G, d->batch);
+            if (split) hipLaunchKernelGGL((k_rows_normsq<DT, 4>), g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
+            else hipLaunchKernelGGL((k_rows_normsq<DT, 1>), g1, dim3(256), 0, st, A, p, p.a_rows, 0, p.T, nsq);
+            WK_LAUNCH_CHECK();
+        }
         if (d->score_algo == WK_SCORE_GEMM) {
             if constexpr (DT == WK_BF16) {
                 double *nsq_cand = reinterpret_cast<double *>(wsp + ws.nsq_cand);
@@ -636,12 +814,21 @@ wk_status launch_all(const wk_compress_desc *d, const CompressDims &p, const WsL
                 return WK_ERR_UNSUPPORTED;
             }
         } else {
-            double *mean_partial = reinterpret_cast<double *>(wsp + ws.mean_partial);
-            hipLaunchKernelGGL(k_anchor_mean_partial<DT>, dim3(p.H, kMeanSplits, d->batch), dim3(256), 0, st, A, p,
-                               nsq, mean_partial);
-            WK_LAUNCH_CHECK();
-            hipLaunchKernelGGL(k_anchor_mean_finish, dim3(p.H, d->batch), dim3(WK_D), 0, st, mean_partial, p, mean);
-            WK_LAUNCH_CHECK();
+            if (fuse.use) {
+                float *fpartial = reinterpret_cast<float *>(wsp + ws.mean_partial);
+                const wk_status rc = launch_norm_mean<DT>(fuse, A, p, d->batch, fpartial, st);
+                if (rc != WK_OK) return rc;
+                hipLaunchKernelGGL(k_anchor_mean_fold, dim3(p.H, d->batch), dim3(WK_D), 0, st, fpartial, p, fuse.n_splits,
+                                   mean);
+                WK_LAUNCH_CHECK();
+            } else {
+                double *mean_partial = reinterpret_cast<double *>(wsp + ws.mean_partial);
+                hipLaunchKernelGGL(k_anchor_mean_partial<DT>, dim3(p.H, kMeanSplits, d->batch), dim3(256), 0, st, A, p,
+                                   nsq, mean_partial);
+                WK_LAUNCH_CHECK();
+                hipLaunchKernelGGL(k_anchor_mean_finish, dim3(p.H, d->batch), dim3(WK_D), 0, st, mean_partial, p, mean);
+                WK_LAUNCH_CHECK();
+            }
             dim3 g3((p.n_cand + rows_pb - 1) / rows_pb, p.G, d->batch);
             if (split) hipLaunchKernelGGL((k_score_factored<DT, 4>), g3, dim3(256), 0, st, Kc, p, mean, scores);
             else hipLaunchKernelGGL((k_score_factored<DT, 1>), g3, dim3(256), 0, st, Kc, p, mean, scores);
