@@ -77,6 +77,32 @@ def test_batch_of_chunks_and_external_anchor():
         _compare_chunk(cfg, K[b], V[b], A[b], gi[b], gK[b], gV[b], gs[b], wk.WK_HEADS_SHARED, cfg.rho, cfg.ratio_kind)
 
 
+@pytest.mark.parametrize("ci,H,T,F,batch,dtype", [
+    (1, 4, 300, 2, 128, ws.configs.DT_F32),      # 3 head rows per lane group, fp32
+    (1, 12, 280, 3, 128, ws.configs.DT_BF16),    # 3, bf16, T not a multiple of the tokens per workgroup
+    (1, 33, 200, 2, 192, ws.configs.DT_BF16),    # 10, heads not a multiple of 4
+    (0, 48, 140, 1, 256, ws.configs.DT_BF16),    # 16, external anchor
+])
+def test_batches_that_take_the_one_pass_anchor_kernel(ci, H, T, F, batch, dtype):
+    """Batches with T * batch >= 8 * 4096 tokens: anchor norms and the normalised anchor mean come from the
+    one-pass kernel, in each of its three sizes.  Several chunks of the batch against the whole oracle."""
+    cfg = ws.get_config(ci).with_(H=H, T=T, F=F, dtype=dtype)
+    assert T * batch >= 8 * 4096
+    picks = [0, 1, batch // 2, batch - 1]
+    base = {c: ws.make_chunk(cfg, c) for c in picks}
+    idx = [picks[b % len(picks)] for b in range(batch)]
+    K = torch.stack([base[c][0] for c in idx])
+    V = torch.stack([base[c][1] for c in idx])
+    A = torch.stack([base[c][2] for c in idx]) if cfg.anchor_mode == wk.WK_ANCHOR_EXTERNAL else None
+    gi, gK, gV, gs, _ = _gpu_compress(cfg, K, V, A, batch=batch, rho=0.75)
+    for b in [0, 1, 2, 3, batch - 1]:
+        _compare_chunk(cfg, K[b], V[b], None if A is None else A[b], gi[b], gK[b], gV[b], gs[b], wk.WK_HEADS_SHARED,
+                       0.75, cfg.ratio_kind)
+    # equal chunks of the batch give equal results, whichever workgroups served them
+    for b in range(len(picks), batch):
+        assert np.array_equal(gi[b], gi[b % len(picks)]) and np.array_equal(gs[b], gs[b % len(picks)])
+
+
 @pytest.mark.parametrize("dtype", [ws.configs.DT_BF16, ws.configs.DT_F32])
 def test_rho_one_is_identity_and_rho_zero_is_anchor_only(dtype):
     cfg = ws.get_config(1).with_(H=2, T=40, dtype=dtype)
